@@ -1,0 +1,225 @@
+// Host side of libgrat: argument validation and dispatch.  No allocation, no synchronisation.
+#include <cmath>
+#include <cstdint>
+
+#include "grat_common.h"
+
+namespace grat {
+namespace {
+
+constexpr int64_t kMaxElems = (int64_t)1 << 31;
+constexpr int32_t kMaxListLen = 8192;
+
+// Validate (ndim, grid, group) and normalise to three axes by prepending unit axes.
+grat_status make_geometry(int32_t ndim, const int32_t* grid, const int32_t* group, Geometry* out) {
+    if (!grid || !group) return GRAT_ERR_NULL;
+    if (ndim < 1 || ndim > 3) return GRAT_ERR_BAD_DIMS;
+    Geometry geo;
+    int64_t n = 1, ng = 1, G = 1;
+    for (int k = 0; k < 3; ++k) {
+        const int src = k - (3 - ndim);
+        const int32_t T = src >= 0 ? grid[src] : 1;
+        const int32_t g = src >= 0 ? group[src] : 1;
+        if (T < 1 || g < 1) return GRAT_ERR_BAD_DIMS;
+        geo.T[k] = T;
+        geo.g[k] = g;
+        geo.G[k] = (T + g - 1) / g;
+        n *= T;
+        ng *= g;
+        G *= geo.G[k];
+        if (n >= kMaxElems || ng >= kMaxElems) return GRAT_ERR_BAD_DIMS;
+    }
+    geo.n_tokens = n;
+    geo.group_tokens = (int32_t)ng;
+    geo.num_groups = (int32_t)G;
+    *out = geo;
+    return GRAT_OK;
+}
+
+grat_status make_radius(int32_t ndim, grat_pattern pattern, const int32_t* radius, int32_t out[3]) {
+    out[0] = out[1] = out[2] = 0;
+    if (pattern != GRAT_BLOCK) return GRAT_OK;
+    if (!radius) return GRAT_ERR_NULL;
+    for (int k = 0; k < ndim; ++k) {
+        if (radius[k] < 0) return GRAT_ERR_BAD_DIMS;
+        out[k + (3 - ndim)] = radius[k];
+    }
+    return GRAT_OK;
+}
+
+bool valid_pattern(grat_pattern p) {
+    return p == GRAT_BLOCK || p == GRAT_CROSS || p == GRAT_CROSS_PLANES || p == GRAT_DENSE;
+}
+
+int64_t longest_list(const Geometry& geo, int32_t ndim, grat_pattern pattern, const int32_t r[3]) {
+    const int first = 3 - ndim;
+    int64_t v;
+    switch (pattern) {
+        case GRAT_BLOCK:
+            v = 1;
+            for (int k = first; k < 3; ++k) v *= std::min<int64_t>(2 * (int64_t)r[k] + 1, geo.G[k]);
+            return v;
+        case GRAT_CROSS:
+            v = -(ndim - 1);
+            for (int k = first; k < 3; ++k) v += geo.G[k];
+            return v;
+        case GRAT_CROSS_PLANES:
+            v = 1;
+            for (int k = first; k < 3; ++k) v *= geo.G[k] - 1;
+            return geo.num_groups - v;
+        default:
+            return geo.num_groups;
+    }
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Checks shared by the grouped and the dense attention entry points.
+grat_status check_tensors(const void* Q, const void* K, const void* V, void* O, grat_dtype dtype,
+                          int32_t batch, int32_t heads, int32_t head_dim, int64_t n_tokens,
+                          int64_t stride_b, int64_t stride_h, int64_t stride_n, float scale) {
+    if (!Q || !K || !V || !O) return GRAT_ERR_NULL;
+    if (batch < 1 || heads < 1 || head_dim < 1 || n_tokens < 1) return GRAT_ERR_BAD_DIMS;
+    if (!(scale > 0.f) || !std::isfinite(scale)) return GRAT_ERR_BAD_DIMS;
+    if (stride_n < head_dim || stride_b < 0 || stride_h < 0) return GRAT_ERR_BAD_DIMS;
+    if (dtype != GRAT_BF16 && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
+    if (dtype == GRAT_BF16 && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
+    if (dtype == GRAT_F32 && head_dim != 64 && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
+    // rows are read and written as 16-byte vectors
+    const int vec = dtype == GRAT_BF16 ? 8 : 4;
+    if (stride_n % vec || stride_b % vec || stride_h % vec) return GRAT_ERR_UNSUPPORTED;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return GRAT_ERR_UNSUPPORTED;
+    if ((n_tokens - 1) * stride_n + head_dim >= kMaxElems) return GRAT_ERR_UNSUPPORTED;
+    if ((int64_t)batch * heads >= ((int64_t)1 << 24)) return GRAT_ERR_UNSUPPORTED;
+    return GRAT_OK;
+}
+
+}  // namespace
+}  // namespace grat
+
+using namespace grat;
+
+extern "C" grat_status grat_block_list_shape(int32_t ndim, const int32_t* grid, const int32_t* group,
+                                             grat_pattern pattern, const int32_t* radius,
+                                             int32_t* num_groups, int32_t* max_kv) {
+    if (!num_groups || !max_kv) return GRAT_ERR_NULL;
+    Geometry geo;
+    grat_status st = make_geometry(ndim, grid, group, &geo);
+    if (st != GRAT_OK) return st;
+    if (!valid_pattern(pattern)) return GRAT_ERR_BAD_PATTERN;
+    int32_t r[3];
+    st = make_radius(ndim, pattern, radius, r);
+    if (st != GRAT_OK) return st;
+    *num_groups = geo.num_groups;
+    *max_kv = (int32_t)longest_list(geo, ndim, pattern, r);
+    return GRAT_OK;
+}
+
+extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int32_t* group,
+                                              grat_pattern pattern, const int32_t* radius,
+                                              int32_t* d_kv_count, int32_t* d_kv_index,
+                                              int32_t max_kv, void* hip_stream) {
+    if (!d_kv_count || !d_kv_index) return GRAT_ERR_NULL;
+    Geometry geo;
+    grat_status st = make_geometry(ndim, grid, group, &geo);
+    if (st != GRAT_OK) return st;
+    if (!valid_pattern(pattern)) return GRAT_ERR_BAD_PATTERN;
+    int32_t r[3];
+    st = make_radius(ndim, pattern, radius, r);
+    if (st != GRAT_OK) return st;
+    if (max_kv < longest_list(geo, ndim, pattern, r)) return GRAT_ERR_BUFFER_TOO_SMALL;
+    if ((int64_t)geo.num_groups * max_kv >= kMaxElems) return GRAT_ERR_UNSUPPORTED;
+    const hipError_t e = launch_build_block_lists(geo, ndim, pattern, r, d_kv_count, d_kv_index,
+                                                  max_kv, (hipStream_t)hip_stream);
+    return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
+}
+
+extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void* O,
+                                          grat_dtype dtype, int32_t batch, int32_t heads,
+                                          int32_t head_dim, int64_t stride_b, int64_t stride_h,
+                                          int64_t stride_n, float scale, int32_t ndim,
+                                          const int32_t* grid, const int32_t* group,
+                                          const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                          int32_t max_kv, void* hip_stream) {
+    if (!d_kv_count || !d_kv_index) return GRAT_ERR_NULL;
+    Geometry geo;
+    grat_status st = make_geometry(ndim, grid, group, &geo);
+    if (st != GRAT_OK) return st;
+    st = check_tensors(Q, K, V, O, dtype, batch, heads, head_dim, geo.n_tokens, stride_b, stride_h,
+                       stride_n, scale);
+    if (st != GRAT_OK) return st;
+    for (int k = 0; k < 3; ++k)
+        if (geo.T[k] % geo.g[k]) return GRAT_ERR_INDIVISIBLE;
+    if (max_kv < 1) return GRAT_ERR_BUFFER_TOO_SMALL;
+    if (max_kv > kMaxListLen) return GRAT_ERR_UNSUPPORTED;
+
+    AttnParams p{};
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.stride_b = stride_b; p.stride_h = stride_h; p.stride_n = (int32_t)stride_n;
+    p.batch = batch; p.heads = heads;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    p.geo = geo;
+    p.kv_count = d_kv_count; p.kv_index = d_kv_index; p.max_kv = max_kv;
+    p.n_tokens = (int32_t)geo.n_tokens;
+
+    const int n_g = geo.group_tokens;
+    int bm;   // query rows per workgroup
+    if (dtype == GRAT_BF16) {
+        if (n_g % 64) return GRAT_ERR_UNSUPPORTED;
+        if (n_g > 4096) return GRAT_ERR_UNSUPPORTED;   // intra-group offset table lives in LDS
+        bm = n_g % 256 == 0 ? 256 : (n_g % 128 == 0 ? 128 : 64);
+    } else {
+        bm = 64;
+    }
+    p.q_tiles = (n_g + bm - 1) / bm;
+    const int64_t total = (int64_t)batch * heads * geo.num_groups * p.q_tiles;
+    if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
+    p.total_tiles = (int32_t)total;
+
+    const hipError_t e = dtype == GRAT_BF16
+                             ? launch_attn_bf16(p, false, (hipStream_t)hip_stream)
+                             : launch_attn_f32(p, head_dim, false, (hipStream_t)hip_stream);
+    return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
+}
+
+extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, const void* V, void* O,
+                                                grat_dtype dtype, int32_t batch, int32_t heads,
+                                                int64_t n_tokens, int32_t head_dim,
+                                                int64_t stride_b, int64_t stride_h,
+                                                int64_t stride_n, float scale, void* hip_stream) {
+    if (n_tokens >= kMaxElems) return GRAT_ERR_BAD_DIMS;
+    grat_status st = check_tensors(Q, K, V, O, dtype, batch, heads, head_dim, n_tokens, stride_b,
+                                   stride_h, stride_n, scale);
+    if (st != GRAT_OK) return st;
+
+    AttnParams p{};
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.stride_b = stride_b; p.stride_h = stride_h; p.stride_n = (int32_t)stride_n;
+    p.batch = batch; p.heads = heads;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    p.n_tokens = (int32_t)n_tokens;
+    const int bm = dtype == GRAT_BF16 ? 256 : 64;
+    p.q_tiles = (int32_t)((n_tokens + bm - 1) / bm);
+    const int64_t total = (int64_t)batch * heads * p.q_tiles;
+    if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
+    p.total_tiles = (int32_t)total;
+
+    const hipError_t e = dtype == GRAT_BF16
+                             ? launch_attn_bf16(p, true, (hipStream_t)hip_stream)
+                             : launch_attn_f32(p, head_dim, true, (hipStream_t)hip_stream);
+    return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
+}
+
+extern "C" const char* grat_status_string(grat_status status) {
+    switch (status) {
+        case GRAT_OK: return "ok";
+        case GRAT_ERR_NULL: return "a required pointer is NULL";
+        case GRAT_ERR_BAD_DIMS: return "bad dimensions, radius, strides or scale";
+        case GRAT_ERR_INDIVISIBLE: return "a group dim does not divide its grid dim";
+        case GRAT_ERR_BAD_PATTERN: return "unknown pattern";
+        case GRAT_ERR_BUFFER_TOO_SMALL: return "max_kv is smaller than the longest list";
+        case GRAT_ERR_UNSUPPORTED: return "shape, dtype, alignment or size not supported";
+        case GRAT_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}

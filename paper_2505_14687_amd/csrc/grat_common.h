@@ -1,0 +1,54 @@
+// Internal declarations shared by the host entry points and the kernels of libgrat.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "grat.h"
+
+namespace grat {
+
+// Grid / group geometry normalised to three axes (missing leading axes have extent 1).
+struct Geometry {
+    int32_t T[3];   // token grid
+    int32_t g[3];   // tokens per group along each axis
+    int32_t G[3];   // groups along each axis, ceil(T/g)
+    int32_t num_groups;
+    int32_t group_tokens;  // g0*g1*g2
+    int64_t n_tokens;
+};
+
+struct AttnParams {
+    const void* Q;
+    const void* K;
+    const void* V;
+    void* O;
+    int64_t stride_b, stride_h;
+    int32_t stride_n;
+    int32_t batch, heads;
+    float scale_log2;          // scale * log2(e)
+    Geometry geo;
+    const int32_t* kv_count;
+    const int32_t* kv_index;
+    int32_t max_kv;
+    int32_t n_tokens;          // dense path: sequence length
+    int32_t q_tiles;           // query tiles per group (grouped) or per head (dense)
+    int32_t total_tiles;       // batch * heads * (groups *) q_tiles
+};
+
+// Launchers: each returns the hipError_t of its launch.
+hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern pattern,
+                                    const int32_t radius[3], int32_t* d_kv_count,
+                                    int32_t* d_kv_index, int32_t max_kv, hipStream_t stream);
+hipError_t launch_attn_f32(const AttnParams& p, int head_dim, bool dense, hipStream_t stream);
+hipError_t launch_attn_bf16(const AttnParams& p, bool dense, hipStream_t stream);
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
+// contiguous range of the logical tile order instead, so that tiles sharing K/V meet in one L2.
+constexpr int kNumXcd = 8;
+__device__ __forceinline__ int xcd_contiguous_tile(int block, int total) {
+    const int per = (total + kNumXcd - 1) / kNumXcd;
+    return (block % kNumXcd) * per + block / kNumXcd;   // may be >= total: caller exits
+}
+inline int xcd_padded_blocks(int total) { return ((total + kNumXcd - 1) / kNumXcd) * kNumXcd; }
+
+}  // namespace grat

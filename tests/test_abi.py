@@ -1,0 +1,100 @@
+"""The C-ABI library loads, exports every symbol the header declares, and validates its
+arguments on the host (no launch happens on these paths, so no GPU is needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_14687_amd as grat
+from paper_2505_14687_amd import grat as binding
+from paper_2505_14687_amd.build import LIB_PATH, ROOT
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "grat.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(grat_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    L = ctypes.CDLL(LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    L = grat.lib()
+    seen = {L.grat_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and all(s for s in seen)
+    assert L.grat_status_string(0) == b"ok"
+
+
+def test_block_list_shape_closed_forms():
+    f = grat.grat_block_list_shape
+    assert f((32, 32), (8, 8), "block", (1, 1)) == (16, 9)
+    assert f((128, 128), (16, 16), "block", (2, 2)) == (64, 25)
+    assert f((128, 128), (16, 16), "block", (20, 0)) == (64, 8)
+    assert f((512, 512), (16, 16), "cross") == (1024, 63)
+    assert f((30, 48, 80), (2, 8, 8), "block", (1, 1, 1)) == (900, 27)
+    assert f((30, 48, 80), (2, 8, 8), "cross") == (900, 29)
+    assert f((30, 48, 80), (2, 8, 8), "cross_planes") == (900, 270)
+    assert f((30, 48, 80), (2, 8, 8), "dense") == (900, 900)
+    assert f((130, 70), (16, 16), "cross") == (9 * 5, 13)      # ragged last groups count
+    assert f((100,), (10,), "cross_planes") == (10, 1)
+
+
+def status_of(fn):
+    with pytest.raises(grat.GratError) as e:
+        fn()
+    return e.value.status
+
+
+def test_shape_argument_errors():
+    f = grat.grat_block_list_shape
+    assert status_of(lambda: f((32, 32, 32, 32), (8, 8, 8, 8), "cross")) == 2
+    assert status_of(lambda: f((32, 0), (8, 8), "cross")) == 2
+    assert status_of(lambda: f((32, 32), (8, -8), "cross")) == 2
+    assert status_of(lambda: f((32, 32), (8, 8), "block", (1, -1))) == 2
+    assert status_of(lambda: f((32, 32), (8, 8), "block", None)) == 1
+    assert status_of(lambda: f((32, 32), (8, 8), 9)) == 4
+
+
+def test_attention_argument_errors_return_before_any_launch():
+    L = grat.lib()
+    i32x2 = ctypes.c_int32 * 2
+    fake = 0x1000   # never dereferenced: every call below fails validation first
+    def call(Q=fake, K=fake, V=fake, O=fake, dtype=0, batch=1, heads=2, d=128, sb=0, sh=4096 * 128,
+             sn=128, scale=0.1, grid=(64, 64), group=(16, 16), cnt=fake, idx=fake, max_kv=9):
+        return L.grat_attention_fwd(Q, K, V, O, dtype, batch, heads, d, sb, sh, sn, scale, 2,
+                                    i32x2(*grid), i32x2(*group), cnt, idx, max_kv, None)
+    assert call(Q=None) == 1 and call(O=None) == 1 and call(cnt=None) == 1
+    assert call(batch=0) == 2 and call(scale=0.0) == 2 and call(scale=float("nan")) == 2
+    assert call(sn=64) == 2
+    assert call(grid=(64, 60)) == 3
+    assert call(d=64) == 6                       # bf16 needs head_dim 128
+    assert call(dtype=1, d=96) == 6
+    assert call(dtype=5) == 6
+    assert call(group=(4, 4)) == 6               # 16-token groups on the bf16 path
+    assert call(sn=132) == 6                     # rows not 16-byte aligned
+    assert call(Q=fake + 2) == 6
+    assert call(max_kv=0) == 5
+    assert call(max_kv=100000) == 6
+    assert call(grid=(1 << 15, 1 << 15), group=(16, 16)) == 6   # offsets beyond 2^31 elements
+    d = L.grat_dense_attention_fwd
+    assert d(fake, fake, fake, None, 0, 1, 1, 100, 128, 0, 0, 128, 0.1, None) == 1
+    assert d(fake, fake, fake, fake, 0, 1, 1, 0, 128, 0, 0, 128, 0.1, None) == 2
+    assert d(fake, fake, fake, fake, 0, 1, 1, 100, 32, 0, 0, 128, 0.1, None) == 6
+    b = L.grat_build_block_lists
+    assert b(2, i32x2(64, 64), i32x2(16, 16), 0, i32x2(1, 1), fake, fake, 8, None) == 5
+    assert b(2, i32x2(64, 64), i32x2(16, 16), 0, i32x2(1, 1), None, fake, 9, None) == 1
+    assert b(2, i32x2(64, 64), i32x2(16, 16), 7, i32x2(1, 1), fake, fake, 9, None) == 4
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    x = torch.zeros(1, 1, 64, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        grat.grat_dense_attention_fwd(x, x, x, 0.1, out=torch.zeros_like(x))
