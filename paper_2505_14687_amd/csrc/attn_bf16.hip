@@ -5,67 +5,98 @@
 // tile: no masking inside tiles, only a list walk around them.
 //
 // Work split: one workgroup = NWAVES wavefronts = 32*NWAVES queries of ONE group; each wave
-// owns 32 queries.  K/V of the listed groups are gathered from row-major token order (rows of a
-// group are runs of g_last contiguous tokens) into LDS in tiles of 64 tokens, double buffered.
+// owns 32 queries.  K/V of the listed groups are gathered from row-major token order (a group's
+// rows are runs of g_last contiguous tokens) straight into LDS with global_load_lds_dwordx4,
+// in tiles of 64 tokens, double buffered; no registers are staged and nothing is permuted in
+// HBM.
 //
 // MFMA formulation (v_mfma_f32_32x32x16_bf16, 64-lane waves), "transposed" so that softmax
 // statistics never cross lanes except once between the two halves of the wave:
 //   S^T[key, query] = K_tile (A operand, rows = keys, from LDS) x Q^T (B operand, registers)
 //       -> lane (query = lane % 32, half = lane / 32) holds 16 keys of that query per 32-key
 //          block: key = 8*(r/4) + 4*half + r%4 for accumulator register r.
-//   O^T[dim, query] += V^T_tile (A operand, rows = head dims, from LDS) x P^T (B operand)
+//   O^T[dim, query] += V^T_tile (A operand, rows = head dims) x P^T (B operand)
 //       -> P^T is exactly the S^T accumulator layout if the contraction index of the second
-//          product is enumerated in that same (r, half) order; V^T is stored in LDS with its
-//          token axis permuted to match, so P never leaves the lane's registers.
-// Softmax runs in base 2 with scale*log2(e) folded into one FMA per score; running max, sum and
-// the O accumulator stay fp32; P is rounded to bf16 (RNE) for the second product.
+//          product is enumerated in that same (r, half) order, so P never leaves the lane's
+//          registers; the matching V^T fragments come out of the row-major V tile through the
+//          LDS transpose read ds_read_b64_tr_b16.
+// Softmax runs in base 2 with scale*log2(e) folded into one FMA per score; the running
+// reference maximum, the sum and the O accumulator stay fp32; P is rounded to bf16 (RNE) for
+// the second product and the row sum is taken over those rounded weights.
+//
+// Schedule: the waves of a workgroup form two sets that run half a tile apart.  While one set
+// issues its matrix block (PV of the previous tile, then QK of the current one), the other runs
+// its softmax block on the vector ALU, and they swap at a barrier; the matrix pipe and the
+// vector ALU of every SIMD are thus fed by different waves at any time.
 #include "grat_common.h"
 
 namespace grat {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kD = 128;        // head_dim
-constexpr int kBN = 64;        // KV tokens per LDS tile
-constexpr int kKPitch = 136;   // bf16 per sK row (272 B: 16-lane b128 reads hit 64 distinct banks)
-constexpr int kVPitch = 72;    // bf16 per sVt row (144 B)
+#define LDS_PTR(T) __attribute__((address_space(3))) T*
+#define GLOBAL_PTR(T) __attribute__((address_space(1))) T*
+
+constexpr int kD = 128;               // head_dim
+constexpr int kBN = 64;               // KV tokens per LDS tile
+constexpr int kRowBytes = kD * 2;     // 256 B per token row
+constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB
+constexpr float kRescaleThreshold = 8.f;      // log2 units: P <= 2^8 before a rescale is forced
+
+// LDS tiles are unpadded [64 rows][16 chunks of 16 B]; the chunk index is XOR-swizzled per row so
+// that the fragment reads are bank-conflict free.  K is read with ds_read_b128 by lanes holding
+// consecutive rows: spread rows over all 16 chunk positions (and keep the two dim-halves of a
+// row apart).  V is read with the 8-byte transpose read by 4 rows x 4 chunks at a time: move
+// each of 4 consecutive rows to a different group of 4 chunks.
+__device__ __forceinline__ int k_swizzle(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
+__device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 2; }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// max over the two lanes that hold the same query (lane and lane ^ 32)
-__device__ __forceinline__ float max_across_halves(float x) {
-    return fmaxf(x, __shfl_xor(x, 32));
+// Exchange between the two lanes that hold the same query (lane and lane ^ 32) with one
+// v_permlane32_swap.  The two results are copied to scalars before they are reinterpreted:
+// a bit cast applied directly to a vector element reads element 0 with this compiler.
+__device__ __forceinline__ void swap_halves(float x, float& lower, float& upper) {
+    const uint32_t a = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    const uint32_t r0 = r[0], r1 = r[1];
+    lower = __builtin_bit_cast(float, r0);   // value held by the lane with the same query, half 0
+    upper = __builtin_bit_cast(float, r1);   // ... half 1
 }
-__device__ __forceinline__ float sum_across_halves(float x) { return x + __shfl_xor(x, 32); }
+__device__ __forceinline__ float max_across_halves(float x) {
+    float lo, hi;
+    swap_halves(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float sum_across_halves(float x) {
+    float lo, hi;
+    swap_halves(x, lo, hi);
+    return lo + hi;
+}
 
 template <int NWAVES, bool DENSE>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
     constexpr int NT = NWAVES * 64;
     constexpr int BM = NWAVES * 32;
-    // K tile chunks: 64 tokens x 16 chunks of 8 bf16.  V units: 16 token quads x 16 dim chunks.
-    // With 512 threads the upper half of the block loads K and the lower half V; with fewer
-    // threads everyone does both.
-    constexpr bool SPLIT = NT == 512;
-    constexpr int KT = SPLIT ? 256 : NT;          // threads loading K
-    constexpr int VT = SPLIT ? 256 : NT;          // threads loading V
-    constexpr int K_PER = 1024 / KT;              // 16-byte chunks per K-loading thread
-    constexpr int V_PER = (256 + VT - 1) / VT;    // 4x8 units per V-loading thread
+    constexpr int LPW = 16 / NWAVES;   // 1-KiB direct loads per wave per 16-KiB tile
 
-    __shared__ __attribute__((aligned(16))) uint16_t sK[2][kBN][kKPitch];
-    __shared__ __attribute__((aligned(16))) uint16_t sVt[2][kD][kVPitch];
+    __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
     extern __shared__ int32_t s_dyn[];   // [n_g] intra-group token offsets, then [max_kv] group origins
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qcol = lane & 31;   // query within the wave's 32
     const int half = lane >> 5;
+    const int set = wave / (NWAVES / 2);   // 0: matrix block first; 1: runs half a tile behind
 
     const int tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
     if (tile >= p.total_tiles) return;
@@ -84,12 +115,12 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     int32_t* s_off = s_dyn;
     int32_t* s_origin = s_dyn + (DENSE ? 0 : geo.group_tokens);
 
-    int n_iters;        // KV tiles to walk
+    int n_tiles;        // KV tiles to walk
     int tiles_per_group = 1;
     int q_row;          // token row of this lane's query
     bool q_valid = true;
     if (DENSE) {
-        n_iters = (p.n_tokens + kBN - 1) / kBN;
+        n_tiles = (p.n_tokens + kBN - 1) / kBN;
         q_row = t_in_head * BM + wave * 32 + qcol;
         q_valid = q_row < p.n_tokens;
         if (!q_valid) q_row = p.n_tokens - 1;
@@ -108,11 +139,12 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         }
         __syncthreads();
         tiles_per_group = n_g / kBN;
-        n_iters = cnt * tiles_per_group;
+        n_tiles = cnt * tiles_per_group;
         const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                              (gamma % geo.G[2]) * geo.g[2];
         q_row = q_origin + s_off[qt * BM + wave * 32 + qcol];
     }
+    if (n_tiles == 0) return;   // an empty list is outside the contract; never touch memory for it
 
     // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
     bf16x8 qf[kD / 16];
@@ -127,172 +159,164 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     for (int db = 0; db < kD / 32; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m_run = -INFINITY;   // running max of raw scores (before scale)
+    f32x16 sacc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+    uint32_t pw[2][8];         // P^T as bf16 pairs, in accumulator register order
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) pw[kb][r] = 0u;
+    float m_ref = -INFINITY;   // reference maximum of raw scores the weights are taken against
     float l_run = 0.f;         // this lane's share of the running sum (its 32 keys per tile)
     const float c = p.scale_log2;
+    const float tau = kRescaleThreshold / c;
 
-    // ---- loader roles -------------------------------------------------------------------
-    const bool loads_k = !SPLIT || tid >= 256;
-    const bool loads_v = !SPLIT || tid < 256;
-    const int ktid = SPLIT ? tid - 256 : tid;
-    const int vtid = tid;
-    uint4 kreg[K_PER];
-    uint4 vreg[V_PER][4];
-
-    // token row of token `kk` (0..63) of KV tile `it`
-    auto kv_row = [&](int gi, int j, int it, int kk) -> int {
-        if (DENSE) return min(it * kBN + kk, p.n_tokens - 1);
-        return s_origin[gi] + s_off[j * kBN + kk];
-    };
-    auto issue_loads = [&](int gi, int j, int it) {
-        if (loads_k) {
+    // ---- tile loads: LPW one-KiB pieces per wave; lane -> (row = 4*piece + lane/16, chunk) ----
+    int load_row[LPW], load_kcol[LPW], load_vcol[LPW];
 #pragma unroll
-            for (int i = 0; i < K_PER; ++i) {
-                const int ch = ktid + i * KT;
-                const int row = kv_row(gi, j, it, ch >> 4);
-                kreg[i] = *(const uint4*)(Kh + (uint32_t)row * stride_n + (ch & 15) * 8);
-            }
+    for (int k = 0; k < LPW; ++k) {
+        const int row = 4 * (wave * LPW + k) + (lane >> 4);
+        load_row[k] = row;
+        load_kcol[k] = ((lane & 15) ^ k_swizzle(row)) * 8;   // element offset of the global chunk
+        load_vcol[k] = ((lane & 15) ^ v_swizzle(row)) * 8;
+    }
+    int gi_k = 0, j_k = 0, gi_v = 0, j_v = 0;   // list entry / tile-in-group of the next K and V tile
+    // The loads are written as inline assembly on purpose: the compiler's wait-count pass treats a
+    // direct-to-LDS load it can see as a possible alias of every later LDS read and would drain
+    // the prefetch before the first fragment read of the same half-step.  Completion is waited for
+    // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
+    auto issue_tile = [&](const uint16_t* base, uint8_t* dst_tile, const int* col, int t, int& gi, int& j) {
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) {
+            int row;
+            if (DENSE) row = min(t * kBN + load_row[k], p.n_tokens - 1);
+            else       row = s_origin[gi] + s_off[j * kBN + load_row[k]];
+            const uint32_t byte_off = ((uint32_t)row * (uint32_t)stride_n + (uint32_t)col[k]) * 2u;
+            // LDS destination of this wave's piece; the hardware adds lane * 16
+            const uint32_t lds_dst = __builtin_amdgcn_readfirstlane(
+                (uint32_t)(uintptr_t)(LDS_PTR(uint8_t))(dst_tile + (wave * LPW + k) * 1024));
+            // (one wait state between the M0 write and the LDS-DMA instruction that reads it)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(lds_dst), "v"(byte_off), "s"(base) : "memory", "m0");
         }
-        if (loads_v) {
-#pragma unroll
-            for (int i = 0; i < V_PER; ++i) {
-                const int u = vtid + i * VT;
-                if (u < 256) {
-                    const int kq = u >> 4, dc = u & 15;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int row = kv_row(gi, j, it, 4 * kq + e);
-                        vreg[i][e] = *(const uint4*)(Vh + (uint32_t)row * stride_n + dc * 8);
-                    }
-                }
-            }
-        }
-    };
-    auto store_tiles = [&](int buf) {
-        if (loads_k) {
-#pragma unroll
-            for (int i = 0; i < K_PER; ++i) {
-                const int ch = ktid + i * KT;
-                *(uint4*)&sK[buf][ch >> 4][(ch & 15) * 8] = kreg[i];
-            }
-        }
-        if (loads_v) {
-#pragma unroll
-            for (int i = 0; i < V_PER; ++i) {
-                const int u = vtid + i * VT;
-                if (u < 256) {
-                    const int kq = u >> 4, dc = u & 15;
-                    // token quad kq lands at permuted quad position (swap its two low bits): the
-                    // order in which the S^T accumulator enumerates keys
-                    const int pos = 4 * ((kq & ~3) | ((kq & 1) << 1) | ((kq >> 1) & 1));
-                    const uint32_t* w0 = (const uint32_t*)&vreg[i][0];
-                    const uint32_t* w1 = (const uint32_t*)&vreg[i][1];
-                    const uint32_t* w2 = (const uint32_t*)&vreg[i][2];
-                    const uint32_t* w3 = (const uint32_t*)&vreg[i][3];
-#pragma unroll
-                    for (int dw = 0; dw < 4; ++dw) {
-                        uint2 even, odd;   // dims 2*dw and 2*dw+1 of the chunk, 4 tokens each
-                        even.x = (w0[dw] & 0xffffu) | (w1[dw] << 16);
-                        even.y = (w2[dw] & 0xffffu) | (w3[dw] << 16);
-                        odd.x = (w0[dw] >> 16) | (w1[dw] & 0xffff0000u);
-                        odd.y = (w2[dw] >> 16) | (w3[dw] & 0xffff0000u);
-                        *(uint2*)&sVt[buf][dc * 8 + 2 * dw][pos] = even;
-                        *(uint2*)&sVt[buf][dc * 8 + 2 * dw + 1][pos] = odd;
-                    }
-                }
-            }
-        }
+        if (!DENSE && ++j == tiles_per_group) { j = 0; ++gi; }
     };
 
-    if (n_iters == 0) return;   // an empty list is outside the contract; never touch memory for it
+    // ---- fragment addresses ----------------------------------------------------------------
+    // K (A operand of S^T): row 32*kb + qcol, chunk (2*ks + half) ^ swizzle(row)
+    const int k_lane_base = qcol * kRowBytes;
+    const int k_x = k_swizzle(qcol) ^ half;          // (2*ks + half) ^ sw == (2*ks) ^ (sw ^ half)
+    // V (A operand of O^T) via transpose reads: 16-lane block -> (e = row in quad, cq = 4-dim column)
+    const int tr_e = (lane & 15) >> 2, tr_cq = lane & 3, tr_dsel = (lane >> 4) & 1;
+    const int v_lane_base = (4 * half + tr_e) * kRowBytes + 8 * (tr_cq & 1);
+    // chunk = 4*db + 2*dsel + cq/2, swizzled with 4*(row & 3) = 4*e  ->  4*(db ^ e) + 2*dsel + cq/2
+    const int v_chunk_lo = 2 * tr_dsel + (tr_cq >> 1);
 
-    // ---- prologue ------------------------------------------------------------------------
-    int gi_next = 0, j_next = 0;   // list entry / tile-in-group of the NEXT tile to load
-    auto advance = [&]() {
-        if (++j_next == tiles_per_group) { j_next = 0; ++gi_next; }
-    };
-    issue_loads(gi_next, j_next, 0);
-    advance();
-    store_tiles(0);
-    __syncthreads();
-
-    int buf = 0;
-    for (int it = 0; it < n_iters; ++it) {
-        const bool more = it + 1 < n_iters;
-        if (more) {
-            issue_loads(gi_next, j_next, it + 1);
-            advance();
-        }
-
-        // ---- S^T = K_tile x Q^T: two 32-key blocks -------------------------------------
-        f32x16 sacc[2];
+    auto qk_block = [&](int buf) {
+        const uint8_t* kt = sK[buf] + k_lane_base;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-            const uint16_t* arow = &sK[buf][32 * kb + qcol][8 * half];
 #pragma unroll
             for (int ks = 0; ks < kD / 16; ++ks) {
-                const bf16x8 a = *(const bf16x8*)(arow + 16 * ks);
+                const bf16x8 a = *(const bf16x8*)(kt + kb * 32 * kRowBytes + (((2 * ks) ^ k_x) << 4));
                 sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
             }
         }
-
-        // dense tail: keys past the end of the sequence get weight 0
-        if (DENSE && (it + 1) * kBN > p.n_tokens) {
+    };
+    auto pv_block = [&](int buf) {
+        const uint8_t* vt = sV[buf] + v_lane_base;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {   // 16 keys per step
+            const uint32_t* w = &pw[s >> 1][4 * (s & 1)];
+            const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+#pragma unroll
+            for (int db = 0; db < kD / 32; ++db) {
+                const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (LDS_PTR(s16x4))(vt + (16 * s) * kRowBytes + col));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (LDS_PTR(s16x4))(vt + (16 * s + 8) * kRowBytes + col));
+                const bf16x8 a = __builtin_bit_cast(
+                    bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, oacc[db], 0, 0, 0);
+            }
+        }
+    };
+    auto softmax_block = [&](int t) {
+        if (DENSE && (t + 1) * kBN > p.n_tokens) {   // keys past the end of the sequence: weight 0
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int key = it * kBN + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const int key = t * kBN + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
                     if (key >= p.n_tokens) sacc[kb][r] = -INFINITY;
                 }
         }
-
-        // ---- online softmax (base 2) ------------------------------------------------------
         float mx = sacc[0][0];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
         mx = max_across_halves(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);   // first tile: 0
-        const float mc = m_new * c;
-        m_run = m_new;
-        float lsum = 0.f;
-        uint32_t pw[2][8];   // P^T as bf16 pairs, in accumulator register order
+        // Move the reference maximum only when some row outgrew it by more than the threshold:
+        // weights stay <= 2^8, and the O / sum rescale is skipped on most tiles.
+        if (__builtin_amdgcn_ballot_w64(mx > m_ref + tau) != 0) {
+            const float m_new = fmaxf(m_ref, mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // first tile: 0
+            m_ref = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < kD / 32; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        }
+        const float mc = m_ref * c;
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c, -mc));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r + 1], c, -mc));
-                lsum += p0 + p1;
-                pw[kb][r >> 1] = pack_bf16(p0, p1);
+                const uint32_t w = pack_bf16(p0, p1);
+                pw[kb][r >> 1] = w;
+                l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, l_run, false);
             }
-        l_run = fmaf(l_run, alpha, lsum);
-#pragma unroll
-        for (int db = 0; db < kD / 32; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    };
 
-        // ---- O^T += V^T_tile x P^T: four 16-key steps x four 32-dim blocks -----------------
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const uint32_t* w = &pw[s >> 1][4 * (s & 1)];
-            const uint4 braw = make_uint4(w[0], w[1], w[2], w[3]);
-            const bf16x8 b = __builtin_bit_cast(bf16x8, braw);
-#pragma unroll
-            for (int db = 0; db < kD / 32; ++db) {
-                const bf16x8 a = *(const bf16x8*)&sVt[buf][32 * db + qcol][16 * s + 8 * half];
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, oacc[db], 0, 0, 0);
+    // ---- prologue: K tile 0 -----------------------------------------------------------------
+    issue_tile(Kh, sK[0], load_kcol, 0, gi_k, j_k);
+
+    // Half-step h: even h starts with the buffer-swap barrier and the loads of K(h/2 + 1), V(h/2);
+    // odd h starts with a bare barrier that only keeps the two wave sets in antiphase.  Wave set s
+    // runs phase h - s: even phases are matrix blocks, odd phases softmax blocks.  Every wave
+    // executes every barrier of the loop.
+    const int n_half_steps = 2 * n_tiles + 2;
+    for (int h = 0; h < n_half_steps; ++h) {
+        const int t = h >> 1;
+        if ((h & 1) == 0) {
+            __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
+            __syncthreads();   // ... everyone's have, and all reads of the buffers to refill are done
+            if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], load_kcol, t + 1, gi_k, j_k);
+            if (t < n_tiles) issue_tile(Vh, sV[t & 1], load_vcol, t, gi_v, j_v);
+        } else {
+            __builtin_amdgcn_s_barrier();
+        }
+        const int phase = h - set;
+        if (phase >= 0) {
+            const int pt = phase >> 1;   // tile this phase works on
+            if ((phase & 1) == 0) {
+                if (pt >= 1) pv_block((pt - 1) & 1);
+                if (pt < n_tiles) qk_block(pt & 1);
+            } else if (pt < n_tiles) {
+                softmax_block(pt);
             }
         }
-
-        if (more) store_tiles(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
     }
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
