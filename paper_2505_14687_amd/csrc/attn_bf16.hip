@@ -183,26 +183,34 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         load_kcol[k] = ((lane & 15) ^ k_swizzle(row)) * 8;   // element offset of the global chunk
         load_vcol[k] = ((lane & 15) ^ v_swizzle(row)) * 8;
     }
+    // Byte offsets of a tile's rows are looked up one period before the tile is fetched, so the
+    // table reads never sit between a barrier and the loads that follow it.
     int gi_k = 0, j_k = 0, gi_v = 0, j_v = 0;   // list entry / tile-in-group of the next K and V tile
-    // The loads are written as inline assembly on purpose: the compiler's wait-count pass treats a
-    // direct-to-LDS load it can see as a possible alias of every later LDS read and would drain
-    // the prefetch before the first fragment read of the same half-step.  Completion is waited for
-    // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
-    auto issue_tile = [&](const uint16_t* base, uint8_t* dst_tile, const int* col, int t, int& gi, int& j) {
+    uint32_t koff[LPW], voff[LPW];
+    auto tile_offsets = [&](uint32_t (&off)[LPW], const int* col, int t, int& gi, int& j) {
 #pragma unroll
         for (int k = 0; k < LPW; ++k) {
             int row;
             if (DENSE) row = min(t * kBN + load_row[k], p.n_tokens - 1);
             else       row = s_origin[gi] + s_off[j * kBN + load_row[k]];
-            const uint32_t byte_off = ((uint32_t)row * (uint32_t)stride_n + (uint32_t)col[k]) * 2u;
+            off[k] = ((uint32_t)row * (uint32_t)stride_n + (uint32_t)col[k]) * 2u;
+        }
+        if (!DENSE && ++j == tiles_per_group) { j = 0; ++gi; }
+    };
+    // The loads are written as inline assembly on purpose: the compiler's wait-count pass treats a
+    // direct-to-LDS load it can see as a possible alias of every later LDS read and would drain
+    // the prefetch before the first fragment read of the same period.  Completion is waited for
+    // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
+    auto issue_tile = [&](const uint16_t* base, uint8_t* dst_tile, const uint32_t (&off)[LPW]) {
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) {
             // LDS destination of this wave's piece; the hardware adds lane * 16
             const uint32_t lds_dst = __builtin_amdgcn_readfirstlane(
                 (uint32_t)(uintptr_t)(LDS_PTR(uint8_t))(dst_tile + (wave * LPW + k) * 1024));
             // (one wait state between the M0 write and the LDS-DMA instruction that reads it)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(lds_dst), "v"(byte_off), "s"(base) : "memory", "m0");
+                         :: "s"(lds_dst), "v"(off[k]), "s"(base) : "memory", "m0");
         }
-        if (!DENSE && ++j == tiles_per_group) { j = 0; ++gi; }
     };
 
     // ---- fragment addresses ----------------------------------------------------------------
@@ -215,38 +223,75 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // chunk = 4*db + 2*dsel + cq/2, swizzled with 4*(row & 3) = 4*e  ->  4*(db ^ e) + 2*dsel + cq/2
     const int v_chunk_lo = 2 * tr_dsel + (tr_cq >> 1);
 
-    auto qk_block = [&](int buf) {
-        const uint8_t* kt = sK[buf] + k_lane_base;
+    // Matrix block = PV of the previous tile followed by QK of the current one: 32 MFMAs in 8
+    // stages of 4.  Fragments are read from LDS two stages ahead of the MFMAs that use them
+    // (two register sets, fa / fb), so that only the first stage waits for LDS latency; the
+    // scheduling barriers keep the compiler from sinking the reads back to their uses.
+    auto v_frags = [&](bf16x8 (&f)[4], const uint8_t* vt, int s) {   // 16 keys of step s, 4 dim blocks
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int db = 0; db < kD / 32; ++db) {
+            const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_PTR(s16x4))(vt + (16 * s) * kRowBytes + col));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_PTR(s16x4))(vt + (16 * s + 8) * kRowBytes + col));
+            f[db] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+    };
+    auto k_frags = [&](bf16x8 (&f)[4], const uint8_t* kt, int j) {   // dims 32*j .. 32*j+31, both key blocks
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const int kb = i & 1, ks = 2 * j + (i >> 1);
+            f[i] = *(const bf16x8*)(kt + kb * 32 * kRowBytes + (((2 * ks) ^ k_x) << 4));
+        }
+    };
+    auto pv_mfma = [&](const bf16x8 (&f)[4], int s) {
+        const uint32_t* w = &pw[s >> 1][4 * (s & 1)];
+        const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
 #pragma unroll
-            for (int ks = 0; ks < kD / 16; ++ks) {
-                const bf16x8 a = *(const bf16x8*)(kt + kb * 32 * kRowBytes + (((2 * ks) ^ k_x) << 4));
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kb], 0, 0, 0);
+        for (int db = 0; db < kD / 32; ++db)
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], b, oacc[db], 0, 0, 0);
+    };
+    auto qk_mfma = [&](const bf16x8 (&f)[4], int j) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kb = i & 1, ks = 2 * j + (i >> 1);
+            if (ks == 0) {
+                f32x16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], zero, 0, 0, 0);
+            } else {
+                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], sacc[kb], 0, 0, 0);
             }
         }
     };
-    auto pv_block = [&](int buf) {
-        const uint8_t* vt = sV[buf] + v_lane_base;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {   // 16 keys per step
-            const uint32_t* w = &pw[s >> 1][4 * (s & 1)];
-            const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
-#pragma unroll
-            for (int db = 0; db < kD / 32; ++db) {
-                const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (LDS_PTR(s16x4))(vt + (16 * s) * kRowBytes + col));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (LDS_PTR(s16x4))(vt + (16 * s + 8) * kRowBytes + col));
-                const bf16x8 a = __builtin_bit_cast(
-                    bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, oacc[db], 0, 0, 0);
-            }
+#define GRAT_STAGE_END() __builtin_amdgcn_sched_barrier(0)
+    auto matrix_block = [&](bool do_pv, int vbuf, bool do_qk, int kbuf) {
+        const uint8_t* vt = sV[vbuf] + v_lane_base;
+        const uint8_t* kt = sK[kbuf] + k_lane_base;
+        bf16x8 fa[4], fb[4];
+        if (do_pv) {
+            v_frags(fa, vt, 0);
+            v_frags(fb, vt, 1);
+            GRAT_STAGE_END();
+            pv_mfma(fa, 0); v_frags(fa, vt, 2); GRAT_STAGE_END();
+            pv_mfma(fb, 1); v_frags(fb, vt, 3); GRAT_STAGE_END();
+            pv_mfma(fa, 2); if (do_qk) k_frags(fa, kt, 0); GRAT_STAGE_END();
+            pv_mfma(fb, 3); if (do_qk) k_frags(fb, kt, 1); GRAT_STAGE_END();
+        } else {
+            k_frags(fa, kt, 0);
+            k_frags(fb, kt, 1);
+            GRAT_STAGE_END();
+        }
+        if (do_qk) {
+            qk_mfma(fa, 0); k_frags(fa, kt, 2); GRAT_STAGE_END();
+            qk_mfma(fb, 1); k_frags(fb, kt, 3); GRAT_STAGE_END();
+            qk_mfma(fa, 2); GRAT_STAGE_END();
+            qk_mfma(fb, 3);
         }
     };
+#undef GRAT_STAGE_END
     auto softmax_block = [&](int t) {
         if (DENSE && (t + 1) * kBN > p.n_tokens) {   // keys past the end of the sequence: weight 0
 #pragma unroll
@@ -290,33 +335,56 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     };
 
     // ---- prologue: K tile 0 -----------------------------------------------------------------
-    issue_tile(Kh, sK[0], load_kcol, 0, gi_k, j_k);
+    tile_offsets(koff, load_kcol, 0, gi_k, j_k);
+    issue_tile(Kh, sK[0], koff);
+    if (1 < n_tiles) tile_offsets(koff, load_kcol, 1, gi_k, j_k);
+    tile_offsets(voff, load_vcol, 0, gi_v, j_v);
 
-    // Half-step h: even h starts with the buffer-swap barrier and the loads of K(h/2 + 1), V(h/2);
-    // odd h starts with a bare barrier that only keeps the two wave sets in antiphase.  Wave set s
-    // runs phase h - s: even phases are matrix blocks, odd phases softmax blocks.  Every wave
-    // executes every barrier of the loop.
-    const int n_half_steps = 2 * n_tiles + 2;
-    for (int h = 0; h < n_half_steps; ++h) {
-        const int t = h >> 1;
-        if ((h & 1) == 0) {
-            __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
-            __syncthreads();   // ... everyone's have, and all reads of the buffers to refill are done
-            if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], load_kcol, t + 1, gi_k, j_k);
-            if (t < n_tiles) issue_tile(Vh, sV[t & 1], load_vcol, t, gi_v, j_v);
-        } else {
-            __builtin_amdgcn_s_barrier();
+    // One period per KV tile t, two barriers per period.  The "swap" barrier publishes K(t) and
+    // V(t-1) (loaded during the previous period) and frees the other two buffers, which are
+    // refilled with K(t+1) and V(t) right away; the "phase" barrier in the middle of the period
+    // moves no data, it only keeps the two wave sets in antiphase:
+    //   set 0:  swap | PV(t-1) QK(t)    | phase | softmax(t)    |
+    //   set 1:  swap | softmax(t-1)     | phase | PV(t-1) QK(t) |
+    // Both sets execute n_tiles + 1 swap barriers and n_tiles + 1 phase barriers.
+    auto swap_barrier = [&](int t) {
+        __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
+        __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
+        if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], koff);
+        if (t < n_tiles) issue_tile(Vh, sV[t & 1], voff);
+        if (t + 2 < n_tiles) tile_offsets(koff, load_kcol, t + 2, gi_k, j_k);
+        if (t + 1 < n_tiles) tile_offsets(voff, load_vcol, t + 1, gi_v, j_v);
+    };
+    auto phase_barrier = [&]() { __builtin_amdgcn_s_barrier(); };
+
+    if (set == 0) {
+        swap_barrier(0);
+        matrix_block(false, 0, true, 0);
+        phase_barrier();
+        softmax_block(0);
+        for (int t = 1; t < n_tiles; ++t) {
+            swap_barrier(t);
+            matrix_block(true, (t - 1) & 1, true, t & 1);
+            phase_barrier();
+            softmax_block(t);
         }
-        const int phase = h - set;
-        if (phase >= 0) {
-            const int pt = phase >> 1;   // tile this phase works on
-            if ((phase & 1) == 0) {
-                if (pt >= 1) pv_block((pt - 1) & 1);
-                if (pt < n_tiles) qk_block(pt & 1);
-            } else if (pt < n_tiles) {
-                softmax_block(pt);
-            }
+        swap_barrier(n_tiles);
+        matrix_block(true, (n_tiles - 1) & 1, false, 0);
+        phase_barrier();
+    } else {
+        swap_barrier(0);
+        phase_barrier();
+        matrix_block(false, 0, true, 0);
+        for (int t = 1; t < n_tiles; ++t) {
+            swap_barrier(t);
+            softmax_block(t - 1);
+            phase_barrier();
+            matrix_block(true, (t - 1) & 1, true, t & 1);
         }
+        swap_barrier(n_tiles);
+        softmax_block(n_tiles - 1);
+        phase_barrier();
+        matrix_block(true, (n_tiles - 1) & 1, false, 0);
     }
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
