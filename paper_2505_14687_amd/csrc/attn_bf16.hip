@@ -112,8 +112,11 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     uint16_t* Oh = (uint16_t*)p.O + head_off;
     const int stride_n = p.stride_n;
 
-    int32_t* s_off = s_dyn;
-    int32_t* s_origin = s_dyn + (DENSE ? 0 : geo.group_tokens);
+    // byte offsets (row * stride_n * 2): s_rowbytes[t] of intra-group token t relative to its group's
+    // first token, s_origin[i] of the first token of the i-th listed KV group
+    uint32_t* s_rowbytes = (uint32_t*)s_dyn;
+    uint32_t* s_origin = (uint32_t*)s_dyn + (DENSE ? 0 : geo.group_tokens);
+    const uint32_t row_pitch = (uint32_t)stride_n * 2u;   // bytes between consecutive tokens
 
     int n_tiles;        // KV tiles to walk
     int tiles_per_group = 1;
@@ -130,19 +133,19 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];
         for (int t = tid; t < n_g; t += NT)
-            s_off[t] = (t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2];
+            s_rowbytes[t] = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
         const int cnt = p.kv_count[gamma];
         for (int i = tid; i < cnt; i += NT) {
             const int gid = p.kv_index[(int64_t)gamma * p.max_kv + i];
-            s_origin[i] = (gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
-                          (gid % geo.G[2]) * geo.g[2];
+            s_origin[i] = (uint32_t)((gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
+                                     (gid % geo.G[2]) * geo.g[2]) * row_pitch;
         }
         __syncthreads();
         tiles_per_group = n_g / kBN;
         n_tiles = cnt * tiles_per_group;
         const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                              (gamma % geo.G[2]) * geo.g[2];
-        q_row = q_origin + s_off[qt * BM + wave * 32 + qcol];
+        q_row = q_origin + (int)(s_rowbytes[qt * BM + wave * 32 + qcol] / row_pitch);
     }
     if (n_tiles == 0) return;   // an empty list is outside the contract; never touch memory for it
 
@@ -175,33 +178,45 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     const float tau = kRescaleThreshold / c;
 
     // ---- tile loads: LPW one-KiB pieces per wave; lane -> (row = 4*piece + lane/16, chunk) ----
-    int load_row[LPW], load_kcol[LPW], load_vcol[LPW];
+    // Address of a piece = head base + (wave-uniform) byte offset of the tile's first token, kept
+    // in scalar registers, + a per-lane byte offset: row within the group (one table read) plus
+    // the swizzled 16-byte chunk of the row.
+    int load_row[LPW];
+    uint32_t load_kcol[LPW], load_vcol[LPW];
 #pragma unroll
     for (int k = 0; k < LPW; ++k) {
         const int row = 4 * (wave * LPW + k) + (lane >> 4);
         load_row[k] = row;
-        load_kcol[k] = ((lane & 15) ^ k_swizzle(row)) * 8;   // element offset of the global chunk
-        load_vcol[k] = ((lane & 15) ^ v_swizzle(row)) * 8;
+        load_kcol[k] = (uint32_t)(((lane & 15) ^ k_swizzle(row)) * 16);   // byte offset of the global chunk
+        load_vcol[k] = (uint32_t)(((lane & 15) ^ v_swizzle(row)) * 16);
     }
-    // Byte offsets of a tile's rows are looked up one period before the tile is fetched, so the
-    // table reads never sit between a barrier and the loads that follow it.
+    // Offsets of a tile are looked up one period before the tile is fetched, so the table reads
+    // never sit between a barrier and the loads that follow it.
+    struct TileAddr {
+        uint32_t base;        // wave-uniform
+        uint32_t off[LPW];    // per lane
+    };
     int gi_k = 0, j_k = 0, gi_v = 0, j_v = 0;   // list entry / tile-in-group of the next K and V tile
-    uint32_t koff[LPW], voff[LPW];
-    auto tile_offsets = [&](uint32_t (&off)[LPW], const int* col, int t, int& gi, int& j) {
+    TileAddr ka, va;
+    auto tile_addr = [&](TileAddr& a, const uint32_t* col, int t, int& gi, int& j) {
+        if (DENSE) {
+            a.base = (uint32_t)(t * kBN) * row_pitch;
 #pragma unroll
-        for (int k = 0; k < LPW; ++k) {
-            int row;
-            if (DENSE) row = min(t * kBN + load_row[k], p.n_tokens - 1);
-            else       row = s_origin[gi] + s_off[j * kBN + load_row[k]];
-            off[k] = ((uint32_t)row * (uint32_t)stride_n + (uint32_t)col[k]) * 2u;
+            for (int k = 0; k < LPW; ++k)   // rows past the end re-read the last token (masked later)
+                a.off[k] = (uint32_t)min(load_row[k], p.n_tokens - 1 - t * kBN) * row_pitch + col[k];
+        } else {
+            a.base = __builtin_amdgcn_readfirstlane(s_origin[gi]);
+#pragma unroll
+            for (int k = 0; k < LPW; ++k) a.off[k] = s_rowbytes[j * kBN + load_row[k]] + col[k];
+            if (++j == tiles_per_group) { j = 0; ++gi; }
         }
-        if (!DENSE && ++j == tiles_per_group) { j = 0; ++gi; }
     };
     // The loads are written as inline assembly on purpose: the compiler's wait-count pass treats a
     // direct-to-LDS load it can see as a possible alias of every later LDS read and would drain
     // the prefetch before the first fragment read of the same period.  Completion is waited for
     // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
-    auto issue_tile = [&](const uint16_t* base, uint8_t* dst_tile, const uint32_t (&off)[LPW]) {
+    auto issue_tile = [&](const uint16_t* head, uint8_t* dst_tile, const TileAddr& a) {
+        const uint8_t* base = (const uint8_t*)head + a.base;
 #pragma unroll
         for (int k = 0; k < LPW; ++k) {
             // LDS destination of this wave's piece; the hardware adds lane * 16
@@ -209,7 +224,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
                 (uint32_t)(uintptr_t)(LDS_PTR(uint8_t))(dst_tile + (wave * LPW + k) * 1024));
             // (one wait state between the M0 write and the LDS-DMA instruction that reads it)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(lds_dst), "v"(off[k]), "s"(base) : "memory", "m0");
+                         :: "s"(lds_dst), "v"(a.off[k]), "s"(base) : "memory", "m0");
         }
     };
 
@@ -335,10 +350,10 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     };
 
     // ---- prologue: K tile 0 -----------------------------------------------------------------
-    tile_offsets(koff, load_kcol, 0, gi_k, j_k);
-    issue_tile(Kh, sK[0], koff);
-    if (1 < n_tiles) tile_offsets(koff, load_kcol, 1, gi_k, j_k);
-    tile_offsets(voff, load_vcol, 0, gi_v, j_v);
+    tile_addr(ka, load_kcol, 0, gi_k, j_k);
+    issue_tile(Kh, sK[0], ka);
+    if (1 < n_tiles) tile_addr(ka, load_kcol, 1, gi_k, j_k);
+    tile_addr(va, load_vcol, 0, gi_v, j_v);
 
     // One period per KV tile t, two barriers per period.  The "swap" barrier publishes K(t) and
     // V(t-1) (loaded during the previous period) and frees the other two buffers, which are
@@ -350,41 +365,54 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     auto swap_barrier = [&](int t) {
         __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
-        if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], koff);
-        if (t < n_tiles) issue_tile(Vh, sV[t & 1], voff);
-        if (t + 2 < n_tiles) tile_offsets(koff, load_kcol, t + 2, gi_k, j_k);
-        if (t + 1 < n_tiles) tile_offsets(voff, load_vcol, t + 1, gi_v, j_v);
+        if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka);
+        if (t < n_tiles) issue_tile(Vh, sV[t & 1], va);
+    };
+    auto next_offsets = [&](int t) {   // rows of the tiles that swap_barrier(t + 1) will fetch
+        if (t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
+        if (t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
     auto phase_barrier = [&]() { __builtin_amdgcn_s_barrier(); };
+    // The matrix block runs at raised wave priority: an MFMA needs one issue slot in eight, and
+    // must not queue behind the other set's dense stream of vector instructions on the same SIMD.
+    auto matrix_phase = [&](bool do_pv, int vbuf, bool do_qk, int kbuf) {
+        __builtin_amdgcn_s_setprio(3);
+        matrix_block(do_pv, vbuf, do_qk, kbuf);
+        __builtin_amdgcn_s_setprio(0);
+    };
 
     if (set == 0) {
         swap_barrier(0);
-        matrix_block(false, 0, true, 0);
+        matrix_phase(false, 0, true, 0);
         phase_barrier();
+        next_offsets(0);
         softmax_block(0);
         for (int t = 1; t < n_tiles; ++t) {
             swap_barrier(t);
-            matrix_block(true, (t - 1) & 1, true, t & 1);
+            matrix_phase(true, (t - 1) & 1, true, t & 1);
             phase_barrier();
+            next_offsets(t);
             softmax_block(t);
         }
         swap_barrier(n_tiles);
-        matrix_block(true, (n_tiles - 1) & 1, false, 0);
+        matrix_phase(true, (n_tiles - 1) & 1, false, 0);
         phase_barrier();
     } else {
         swap_barrier(0);
+        next_offsets(0);
         phase_barrier();
-        matrix_block(false, 0, true, 0);
+        matrix_phase(false, 0, true, 0);
         for (int t = 1; t < n_tiles; ++t) {
             swap_barrier(t);
+            next_offsets(t);
             softmax_block(t - 1);
             phase_barrier();
-            matrix_block(true, (t - 1) & 1, true, t & 1);
+            matrix_phase(true, (t - 1) & 1, true, t & 1);
         }
         swap_barrier(n_tiles);
         softmax_block(n_tiles - 1);
         phase_barrier();
-        matrix_block(true, (n_tiles - 1) & 1, false, 0);
+        matrix_phase(true, (n_tiles - 1) & 1, false, 0);
     }
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
