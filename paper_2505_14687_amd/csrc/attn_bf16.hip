@@ -45,7 +45,7 @@ constexpr int kD = 128;               // head_dim
 constexpr int kBN = 64;               // KV tokens per LDS tile
 constexpr int kRowBytes = kD * 2;     // 256 B per token row
 constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB
-constexpr float kRescaleThreshold = 8.f;      // log2 units: P <= 2^8 before a rescale is forced
+constexpr float kSumLimit = 0x1p+40f;   // a lane's tile row sum (32 weights) beyond this forces a new reference maximum
 
 // LDS tiles are unpadded [64 rows][16 chunks of 16 B]; the chunk index is XOR-swizzled per row so
 // that the fragment reads are bank-conflict free.  K is read with ds_read_b128 by lanes holding
@@ -175,7 +175,6 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     float m_ref = -INFINITY;   // reference maximum of raw scores the weights are taken against
     float l_run = 0.f;         // this lane's share of the running sum (its 32 keys per tile)
     const float c = p.scale_log2;
-    const float tau = kRescaleThreshold / c;
 
     // ---- tile loads: LPW one-KiB pieces per wave; lane -> (row = 4*piece + lane/16, chunk) ----
     // Address of a piece = head base + (wave-uniform) byte offset of the tile's first token, kept
@@ -282,22 +281,27 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         }
     };
 #define GRAT_STAGE_END() __builtin_amdgcn_sched_barrier(0)
+    // prefetch_pv / prefetch_qk fetch the fragments of the first two stages.
+    bf16x8 fa[4], fb[4];
+    auto prefetch_pv = [&](int vbuf) {
+        const uint8_t* vt = sV[vbuf] + v_lane_base;
+        v_frags(fa, vt, 0);
+        v_frags(fb, vt, 1);
+    };
+    auto prefetch_qk = [&](int kbuf) {
+        const uint8_t* kt = sK[kbuf] + k_lane_base;
+        k_frags(fa, kt, 0);
+        k_frags(fb, kt, 1);
+    };
     auto matrix_block = [&](bool do_pv, int vbuf, bool do_qk, int kbuf) {
         const uint8_t* vt = sV[vbuf] + v_lane_base;
         const uint8_t* kt = sK[kbuf] + k_lane_base;
-        bf16x8 fa[4], fb[4];
+        GRAT_STAGE_END();
         if (do_pv) {
-            v_frags(fa, vt, 0);
-            v_frags(fb, vt, 1);
-            GRAT_STAGE_END();
             pv_mfma(fa, 0); v_frags(fa, vt, 2); GRAT_STAGE_END();
             pv_mfma(fb, 1); v_frags(fb, vt, 3); GRAT_STAGE_END();
             pv_mfma(fa, 2); if (do_qk) k_frags(fa, kt, 0); GRAT_STAGE_END();
             pv_mfma(fb, 3); if (do_qk) k_frags(fb, kt, 1); GRAT_STAGE_END();
-        } else {
-            k_frags(fa, kt, 0);
-            k_frags(fb, kt, 1);
-            GRAT_STAGE_END();
         }
         if (do_qk) {
             qk_mfma(fa, 0); k_frags(fa, kt, 2); GRAT_STAGE_END();
@@ -307,7 +311,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         }
     };
 #undef GRAT_STAGE_END
-    auto softmax_block = [&](int t) {
+    auto softmax_block = [&](int t, bool first_tile) {
         if (DENSE && (t + 1) * kBN > p.n_tokens) {   // keys past the end of the sequence: weight 0
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -317,15 +321,42 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
                     if (key >= p.n_tokens) sacc[kb][r] = -INFINITY;
                 }
         }
-        float mx = sacc[0][0];
+        // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to
+        // be: the common path computes exp2(c*s - c*m_ref) without looking at the tile's own maximum
+        // and checks afterwards that no row sum of this tile left the safe range; only then (and
+        // on the first tile) is the true maximum computed, O and the running sum rescaled, and the
+        // tile's weights recomputed.  Any reference gives the same quotient O / l; this one keeps
+        // every weight below 2^40, which bf16 and the fp32 accumulators hold without loss of relative accuracy.
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        auto weights = [&]() -> float {   // P(t) into pw; returns this lane's share of the tile's row sum
+            const float mc = m_ref * c;
+            float ls = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
-        mx = max_across_halves(mx);
-        // Move the reference maximum only when some row outgrew it by more than the threshold:
-        // weights stay <= 2^8, and the O / sum rescale is skipped on most tiles.
-        if (__builtin_amdgcn_ballot_w64(mx > m_ref + tau) != 0) {
+                for (int r = 0; r < 16; r += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c, -mc));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r + 1], c, -mc));
+                    const uint32_t w = pack_bf16(p0, p1);
+                    pw[kb][r >> 1] = w;
+                    ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, ls, false);
+                }
+            return ls;
+        };
+        float ls = 0.f;
+        bool redo = first_tile;
+        if (!first_tile) {
+            ls = weights();
+            // a row sum above 2^(threshold + 6) (64 weights per lane) or not finite: reference too stale
+            redo = __builtin_amdgcn_ballot_w64(!(ls < kSumLimit)) != 0;
+        }
+        if (redo) {
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+            mx = max_across_halves(mx);
             const float m_new = fmaxf(m_ref, mx);
             const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // first tile: 0
             m_ref = m_new;
@@ -334,33 +365,24 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             for (int db = 0; db < kD / 32; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+            ls = weights();
         }
-        const float mc = m_ref * c;
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c, -mc));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r + 1], c, -mc));
-                const uint32_t w = pack_bf16(p0, p1);
-                pw[kb][r >> 1] = w;
-                l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, l_run, false);
-            }
+        l_run += ls;
     };
 
-    // ---- prologue: K tile 0 -----------------------------------------------------------------
+    // ---- prologue: K tile 0 --------------------------------------------------------------------
     tile_addr(ka, load_kcol, 0, gi_k, j_k);
     issue_tile(Kh, sK[0], ka);
     if (1 < n_tiles) tile_addr(ka, load_kcol, 1, gi_k, j_k);
     tile_addr(va, load_vcol, 0, gi_v, j_v);
 
-    // One period per KV tile t, two barriers per period.  The "swap" barrier publishes K(t) and
-    // V(t-1) (loaded during the previous period) and frees the other two buffers, which are
-    // refilled with K(t+1) and V(t) right away; the "phase" barrier in the middle of the period
-    // moves no data, it only keeps the two wave sets in antiphase:
-    //   set 0:  swap | PV(t-1) QK(t)    | phase | softmax(t)    |
-    //   set 1:  swap | softmax(t-1)     | phase | PV(t-1) QK(t) |
+    // One period per KV tile t, two barriers per period, K and V tiles double buffered (tile t in
+    // buffer t & 1).  The "swap" barrier of period t publishes K(t) and V(t-1), fetched during
+    // period t-1, and frees the buffers of K(t-1) and V(t-2), which are refilled with K(t+1) and
+    // V(t) right away.  The "phase" barrier in the middle of the period moves no data, it only
+    // keeps the two wave sets in antiphase:
+    //   set 0:  swap | PV(t-1) QK(t)   | phase | softmax(t)    |
+    //   set 1:  swap | softmax(t-1)    | phase | PV(t-1) QK(t) |
     // Both sets execute n_tiles + 1 swap barriers and n_tiles + 1 phase barriers.
     auto swap_barrier = [&](int t) {
         __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
@@ -377,6 +399,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // must not queue behind the other set's dense stream of vector instructions on the same SIMD.
     auto matrix_phase = [&](bool do_pv, int vbuf, bool do_qk, int kbuf) {
         __builtin_amdgcn_s_setprio(3);
+        if (do_pv) prefetch_pv(vbuf); else prefetch_qk(kbuf);
         matrix_block(do_pv, vbuf, do_qk, kbuf);
         __builtin_amdgcn_s_setprio(0);
     };
@@ -386,13 +409,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         matrix_phase(false, 0, true, 0);
         phase_barrier();
         next_offsets(0);
-        softmax_block(0);
+        softmax_block(0, true);
         for (int t = 1; t < n_tiles; ++t) {
             swap_barrier(t);
             matrix_phase(true, (t - 1) & 1, true, t & 1);
             phase_barrier();
             next_offsets(t);
-            softmax_block(t);
+            softmax_block(t, false);
         }
         swap_barrier(n_tiles);
         matrix_phase(true, (n_tiles - 1) & 1, false, 0);
@@ -405,12 +428,12 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         for (int t = 1; t < n_tiles; ++t) {
             swap_barrier(t);
             next_offsets(t);
-            softmax_block(t - 1);
+            softmax_block(t - 1, t == 1);
             phase_barrier();
             matrix_phase(true, (t - 1) & 1, true, t & 1);
         }
         swap_barrier(n_tiles);
-        softmax_block(n_tiles - 1);
+        softmax_block(n_tiles - 1, n_tiles == 1);
         phase_barrier();
         matrix_phase(true, (n_tiles - 1) & 1, false, 0);
     }
