@@ -18,6 +18,19 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 
 
+def measured_traffic(workload, pattern):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one
+    for this workload (profiles/attn_bf16_<workload>_<pattern>.md, line 'traffic_bytes_per_launch: N')."""
+    path = os.path.join(ROOT, "profiles", f"attn_bf16_{workload}_{pattern}.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -31,6 +44,7 @@ def main():
     ap.add_argument("--pattern", default="B3")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparison launch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-others", action="store_true", help="skip the workload's other patterns")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -57,6 +71,9 @@ def main():
         return torch.from_numpy(x).cuda()
     Q, K, V = (dev(x) for x in host)
     O = torch.empty_like(Q)
+    # one plain device copy of known size (Q -> O) ahead of everything: the reference against which
+    # the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script are scaled
+    O.copy_(Q)
     torch.cuda.synchronize()
     log(f"inputs: {args.workload} {tuple(Q.shape)} {w.dtype} generated+uploaded in {time.time() - t0:.1f}s")
 
@@ -97,7 +114,7 @@ def main():
 
     extra = {}
     for label, (pat, rad) in w.patterns.items():
-        if label == args.pattern or pat == "dense":
+        if label == args.pattern or pat == "dense" or args.no_others:
             continue
         r = time_pattern(pat, rad, max(3, args.steps // 4), 2)
         extra[label] = {"ms_per_step": round(r["ms_per_step"], 4),
@@ -172,7 +189,8 @@ def main():
                    "step": "grat_build_block_lists + grat_attention_fwd"},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
-                     "traffic": None, "kernel": "attn_bf16_kernel (grouped)",
+                     "traffic": measured_traffic(args.workload, args.pattern),
+                     "kernel": "grat::attn_bf16_kernel<8, false>",
                      "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4)},
         "cpu_baseline": cpu,
         "dense": dense,

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         q_valid = q_row < p.n_tokens;
         if (!q_valid) q_row = p.n_tokens - 1;
     } else {
-        const int gamma = t_in_head / p.q_tiles;
+        const int gamma = strip_order_group(t_in_head / p.q_tiles, geo.G[0] * geo.G[1], geo.G[2], p.strip_w);
         const int qt = t_in_head % p.q_tiles;
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];

@@ -172,6 +172,7 @@ extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const vo
         bm = 64;
     }
     p.q_tiles = (n_g + bm - 1) / bm;
+    p.strip_w = geo.G[2] >= 16 ? 8 : geo.G[2];
     const int64_t total = (int64_t)batch * heads * geo.num_groups * p.q_tiles;
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;

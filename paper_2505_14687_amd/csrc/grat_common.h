@@ -33,6 +33,7 @@ struct AttnParams {
     int32_t n_tokens;          // dense path: sequence length
     int32_t q_tiles;           // query tiles per group (grouped) or per head (dense)
     int32_t total_tiles;       // batch * heads * (groups *) q_tiles
+    int32_t strip_w;           // grouped bf16 path: query groups are walked in column strips this wide
 };
 
 // Launchers: each returns the hipError_t of its launch.
@@ -50,5 +51,18 @@ __device__ __forceinline__ int xcd_contiguous_tile(int block, int total) {
     return (block % kNumXcd) * per + block / kNumXcd;   // may be >= total: caller exits
 }
 inline int xcd_padded_blocks(int total) { return ((total + kNumXcd - 1) / kNumXcd) * kNumXcd; }
+
+// Order in which the query groups of one head are handed to consecutive workgroups: column strips
+// of the group grid, `strip_w` groups wide, each walked row by row.  The ~32 workgroups an XCD
+// runs at a time then cover a compact 2D patch of groups (4 rows x 8 columns for strip_w = 8)
+// whose K/V neighbourhoods overlap in both directions, instead of one long group-row.
+// rows = all leading group axes flattened, cols = the last group axis; returns the linear group id.
+__device__ __forceinline__ int strip_order_group(int u, int rows, int cols, int strip_w) {
+    const int full = cols / strip_w;
+    int s = u / (rows * strip_w), w = strip_w;
+    if (s >= full) { s = full; w = cols - full * strip_w; }
+    const int v = u - s * rows * strip_w;
+    return (v / w) * cols + s * strip_w + v % w;
+}
 
 }  // namespace grat
