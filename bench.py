@@ -1,7 +1,7 @@
 """Benchmark of the GRAT attention hot path on one MI355X.
 
 One step = build the per-group KV block lists + one grat_attention_fwd over the workload
-(Q, K, V resident in HBM).  Prints ONE JSON line; see the design doc for the fields.
+(Q, K, V resident in HBM).  Prints ONE JSON line.
 
     python bench.py [--steps K] [--warmup W] [--workload img8192] [--pattern B3]
 """
@@ -48,8 +48,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this build measures one GPU only (head-sharding across GPUs needs no "
-                 "exchange inside attention; see DESIGN.md). Run with --gpus 1.")
+        sys.exit("bench.py: this build measures one GPU only (heads shard across GPUs with no "
+                 "exchange inside attention, so the one-GPU figure is the per-GPU figure). Run with --gpus 1.")
 
     import numpy as np
     import torch
