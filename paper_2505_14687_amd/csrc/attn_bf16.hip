@@ -20,14 +20,15 @@
 //          product is enumerated in that same (r, half) order, so P never leaves the lane's
 //          registers; the matching V^T fragments come out of the row-major V tile through the
 //          LDS transpose read ds_read_b64_tr_b16.
-// Softmax runs in base 2 with scale*log2(e) folded into one FMA per score; the running
-// reference maximum, the sum and the O accumulator stay fp32; P is rounded to bf16 (RNE) for
-// the second product and the row sum is taken over those rounded weights.
+// Softmax runs in base 2 with scale*log2(e) folded into one FMA per score; the reference
+// maximum, the running sum and the O accumulator stay fp32; P is rounded to bf16 (RNE) for the
+// second product and the row sum is taken over those rounded weights.
 //
-// Schedule: the waves of a workgroup form two sets that run half a tile apart.  While one set
-// issues its matrix block (PV of the previous tile, then QK of the current one), the other runs
-// its softmax block on the vector ALU, and they swap at a barrier; the matrix pipe and the
-// vector ALU of every SIMD are thus fed by different waves at any time.
+// Schedule: one barrier per KV tile.  Within a tile every wave runs, as ONE straight-line
+// block, the QK product of tile t and the weights of tile t next to the PV product of tile t-1
+// (P is double buffered, PV lags QK by a tile), so each stretch of vector-ALU work has
+// independent MFMAs of the same wave to hide behind, and the two waves of a SIMD fill each
+// other's remaining gaps.
 #include "grat_common.h"
 
 namespace grat {
@@ -39,7 +40,6 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
-#define GLOBAL_PTR(T) __attribute__((address_space(1))) T*
 
 constexpr int kD = 128;               // head_dim
 constexpr int kBN = 64;               // KV tokens per LDS tile
@@ -89,14 +89,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 
     __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
-    extern __shared__ int32_t s_dyn[];   // [n_g] intra-group token offsets, then [max_kv] group origins
+    extern __shared__ int32_t s_dyn[];   // [n_g] row offsets inside a group, then [max_kv] group origins
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qcol = lane & 31;   // query within the wave's 32
     const int half = lane >> 5;
-    const int set = wave / (NWAVES / 2);   // 0: matrix block first; 1: runs half a tile behind
 
     const int tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
     if (tile >= p.total_tiles) return;
@@ -157,21 +156,20 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
     }
 
-    f32x16 oacc[kD / 32];
+    f32x16 oacc[kD / 32];                 // O^T accumulator: 4 blocks of 32 head dims
+    f32x16 S[2];                          // S^T of the current tile: 2 blocks of 32 keys
+    uint32_t pwA[2][8], pwB[2][8];        // P^T of two consecutive tiles as bf16 pairs, in accumulator order
 #pragma unroll
     for (int db = 0; db < kD / 32; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    f32x16 sacc[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-    uint32_t pw[2][8];         // P^T as bf16 pairs, in accumulator register order
+        for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) pw[kb][r] = 0u;
+        for (int r = 0; r < 8; ++r) { pwA[kb][r] = 0u; pwB[kb][r] = 0u; }
+    }
     float m_ref = -INFINITY;   // reference maximum of raw scores the weights are taken against
     float l_run = 0.f;         // this lane's share of the running sum (its 32 keys per tile)
     const float c = p.scale_log2;
@@ -189,14 +187,14 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         load_kcol[k] = (uint32_t)(((lane & 15) ^ k_swizzle(row)) * 16);   // byte offset of the global chunk
         load_vcol[k] = (uint32_t)(((lane & 15) ^ v_swizzle(row)) * 16);
     }
-    // Offsets of a tile are looked up one period before the tile is fetched, so the table reads
-    // never sit between a barrier and the loads that follow it.
     struct TileAddr {
         uint32_t base;        // wave-uniform
         uint32_t off[LPW];    // per lane
     };
     int gi_k = 0, j_k = 0, gi_v = 0, j_v = 0;   // list entry / tile-in-group of the next K and V tile
     TileAddr ka, va;
+    // Offsets of a tile are looked up one tile before it is fetched, so the table reads never sit
+    // between a barrier and the loads that follow it.
     auto tile_addr = [&](TileAddr& a, const uint32_t* col, int t, int& gi, int& j) {
         if (DENSE) {
             a.base = (uint32_t)(t * kBN) * row_pitch;
@@ -212,7 +210,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     };
     // The loads are written as inline assembly on purpose: the compiler's wait-count pass treats a
     // direct-to-LDS load it can see as a possible alias of every later LDS read and would drain
-    // the prefetch before the first fragment read of the same period.  Completion is waited for
+    // the prefetch before the first fragment read that follows.  Completion is waited for
     // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
     auto issue_tile = [&](const uint16_t* head, uint8_t* dst_tile, const TileAddr& a) {
         const uint8_t* base = (const uint8_t*)head + a.base;
@@ -237,125 +235,86 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // chunk = 4*db + 2*dsel + cq/2, swizzled with 4*(row & 3) = 4*e  ->  4*(db ^ e) + 2*dsel + cq/2
     const int v_chunk_lo = 2 * tr_dsel + (tr_cq >> 1);
 
-    // Matrix block = PV of the previous tile followed by QK of the current one: 32 MFMAs in 8
-    // stages of 4.  Fragments are read from LDS two stages ahead of the MFMAs that use them
-    // (two register sets, fa / fb), so that only the first stage waits for LDS latency; the
-    // scheduling barriers keep the compiler from sinking the reads back to their uses.
-    auto v_frags = [&](bf16x8 (&f)[4], const uint8_t* vt, int s) {   // 16 keys of step s, 4 dim blocks
+    // QK for the 32-key block kb of the tile in sK[kbuf]: 8 fragment reads, 8 MFMAs
+    auto qk_half = [&](int kbuf, int kb) {
+        const uint8_t* kt = sK[kbuf] + k_lane_base + kb * 32 * kRowBytes;
 #pragma unroll
-        for (int db = 0; db < kD / 32; ++db) {
-            const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (LDS_PTR(s16x4))(vt + (16 * s) * kRowBytes + col));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (LDS_PTR(s16x4))(vt + (16 * s + 8) * kRowBytes + col));
-            f[db] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        }
-    };
-    auto k_frags = [&](bf16x8 (&f)[4], const uint8_t* kt, int j) {   // dims 32*j .. 32*j+31, both key blocks
+        for (int j = 0; j < 2; ++j) {
+            bf16x8 f[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int kb = i & 1, ks = 2 * j + (i >> 1);
-            f[i] = *(const bf16x8*)(kt + kb * 32 * kRowBytes + (((2 * ks) ^ k_x) << 4));
-        }
-    };
-    auto pv_mfma = [&](const bf16x8 (&f)[4], int s) {
-        const uint32_t* w = &pw[s >> 1][4 * (s & 1)];
-        const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            for (int i = 0; i < 4; ++i) f[i] = *(const bf16x8*)(kt + (((2 * (4 * j + i)) ^ k_x) << 4));
 #pragma unroll
-        for (int db = 0; db < kD / 32; ++db)
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], b, oacc[db], 0, 0, 0);
-    };
-    auto qk_mfma = [&](const bf16x8 (&f)[4], int j) {
+            for (int i = 0; i < 4; ++i) {
+                const int ks = 4 * j + i;
+                if (ks == 0) {
+                    f32x16 zero;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int kb = i & 1, ks = 2 * j + (i >> 1);
-            if (ks == 0) {
-                f32x16 zero;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], zero, 0, 0, 0);
-            } else {
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], sacc[kb], 0, 0, 0);
+                    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                    S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], zero, 0, 0, 0);
+                } else {
+                    S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], S[kb], 0, 0, 0);
+                }
             }
         }
     };
-#define GRAT_STAGE_END() __builtin_amdgcn_sched_barrier(0)
-    // prefetch_pv / prefetch_qk fetch the fragments of the first two stages.
-    bf16x8 fa[4], fb[4];
-    auto prefetch_pv = [&](int vbuf) {
+    // PV for the two 16-key steps of key block kb of the tile in sV[vbuf]: 16 transpose reads, 8 MFMAs
+    auto pv_half = [&](int vbuf, int kb, const uint32_t (&pw)[2][8]) {
         const uint8_t* vt = sV[vbuf] + v_lane_base;
-        v_frags(fa, vt, 0);
-        v_frags(fb, vt, 1);
-    };
-    auto prefetch_qk = [&](int kbuf) {
-        const uint8_t* kt = sK[kbuf] + k_lane_base;
-        k_frags(fa, kt, 0);
-        k_frags(fb, kt, 1);
-    };
-    auto matrix_block = [&](bool do_pv, int vbuf, bool do_qk, int kbuf) {
-        const uint8_t* vt = sV[vbuf] + v_lane_base;
-        const uint8_t* kt = sK[kbuf] + k_lane_base;
-        GRAT_STAGE_END();
-        if (do_pv) {
-            pv_mfma(fa, 0); v_frags(fa, vt, 2); GRAT_STAGE_END();
-            pv_mfma(fb, 1); v_frags(fb, vt, 3); GRAT_STAGE_END();
-            pv_mfma(fa, 2); if (do_qk) k_frags(fa, kt, 0); GRAT_STAGE_END();
-            pv_mfma(fb, 3); if (do_qk) k_frags(fb, kt, 1); GRAT_STAGE_END();
-        }
-        if (do_qk) {
-            qk_mfma(fa, 0); k_frags(fa, kt, 2); GRAT_STAGE_END();
-            qk_mfma(fb, 1); k_frags(fb, kt, 3); GRAT_STAGE_END();
-            qk_mfma(fa, 2); GRAT_STAGE_END();
-            qk_mfma(fb, 3);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            bf16x8 f[4];
+#pragma unroll
+            for (int db = 0; db < kD / 32; ++db) {
+                const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
+                const uint8_t* src = vt + (32 * kb + 16 * s2) * kRowBytes + col;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))src);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(src + 8 * kRowBytes));
+                f[db] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+            const uint32_t* w = &pw[kb][4 * s2];
+            const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+#pragma unroll
+            for (int db = 0; db < kD / 32; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], b, oacc[db], 0, 0, 0);
         }
     };
-#undef GRAT_STAGE_END
-    auto softmax_block = [&](int t, bool first_tile) {
-        if (DENSE && (t + 1) * kBN > p.n_tokens) {   // keys past the end of the sequence: weight 0
+    // Weights of key block kb against the current reference maximum; adds this lane's share of the
+    // row sum (taken over the rounded weights) to ls.  The packed dot product does the summing.
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    auto exp_half = [&](int kb, uint32_t (&pw)[2][8], float& ls) {
+        const float mc = m_ref * c;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], c, -mc));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], c, -mc));
+            const uint32_t w = pack_bf16(p0, p1);
+            pw[kb][r >> 1] = w;
+            ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, ls, false);
+        }
+    };
+    auto mask_tail = [&](int t) {   // dense path: keys past the end of the sequence get weight 0
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = t * kBN + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (key >= p.n_tokens) S[kb][r] = -INFINITY;
+            }
+    };
+    // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to be:
+    // the common path computes exp2(c*s - c*m_ref) without looking at the tile's own maximum and
+    // checks afterwards that no row sum of the tile left the safe range.  Only then (and on the
+    // first tile, where m_ref = -inf makes every sum infinite) is the true maximum computed, O and
+    // the running sum rescaled, and the tile's weights recomputed.  Any reference gives the same
+    // quotient O / l; this one keeps every weight below 2^40, which bf16 and the fp32 accumulators
+    // hold without loss of relative accuracy.
+    auto finish_softmax = [&](uint32_t (&pw)[2][8], float ls) {
+        if (__builtin_amdgcn_ballot_w64(!(ls < kSumLimit)) != 0) {
+            float mx = S[0][0];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = t * kBN + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (key >= p.n_tokens) sacc[kb][r] = -INFINITY;
-                }
-        }
-        // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to
-        // be: the common path computes exp2(c*s - c*m_ref) without looking at the tile's own maximum
-        // and checks afterwards that no row sum of this tile left the safe range; only then (and
-        // on the first tile) is the true maximum computed, O and the running sum rescaled, and the
-        // tile's weights recomputed.  Any reference gives the same quotient O / l; this one keeps
-        // every weight below 2^40, which bf16 and the fp32 accumulators hold without loss of relative accuracy.
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-        auto weights = [&]() -> float {   // P(t) into pw; returns this lane's share of the tile's row sum
-            const float mc = m_ref * c;
-            float ls = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c, -mc));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r + 1], c, -mc));
-                    const uint32_t w = pack_bf16(p0, p1);
-                    pw[kb][r >> 1] = w;
-                    ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, ls, false);
-                }
-            return ls;
-        };
-        float ls = 0.f;
-        bool redo = first_tile;
-        if (!first_tile) {
-            ls = weights();
-            // a row sum above 2^(threshold + 6) (64 weights per lane) or not finite: reference too stale
-            redo = __builtin_amdgcn_ballot_w64(!(ls < kSumLimit)) != 0;
-        }
-        if (redo) {
-            float mx = sacc[0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
             mx = max_across_halves(mx);
             const float m_new = fmaxf(m_ref, mx);
             const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // first tile: 0
@@ -365,77 +324,69 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             for (int db = 0; db < kD / 32; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            ls = weights();
+            ls = 0.f;
+            exp_half(0, pw, ls);
+            exp_half(1, pw, ls);
         }
         l_run += ls;
     };
 
-    // ---- prologue: K tile 0 --------------------------------------------------------------------
+    // ---- prologue: K tile 0 -----------------------------------------------------------------
     tile_addr(ka, load_kcol, 0, gi_k, j_k);
     issue_tile(Kh, sK[0], ka);
     if (1 < n_tiles) tile_addr(ka, load_kcol, 1, gi_k, j_k);
     tile_addr(va, load_vcol, 0, gi_v, j_v);
 
-    // One period per KV tile t, two barriers per period, K and V tiles double buffered (tile t in
-    // buffer t & 1).  The "swap" barrier of period t publishes K(t) and V(t-1), fetched during
-    // period t-1, and frees the buffers of K(t-1) and V(t-2), which are refilled with K(t+1) and
-    // V(t) right away.  The "phase" barrier in the middle of the period moves no data, it only
-    // keeps the two wave sets in antiphase:
-    //   set 0:  swap | PV(t-1) QK(t)   | phase | softmax(t)    |
-    //   set 1:  swap | softmax(t-1)    | phase | PV(t-1) QK(t) |
-    // Both sets execute n_tiles + 1 swap barriers and n_tiles + 1 phase barriers.
+    // swap_barrier(t) publishes K(t) and V(t-1), fetched during the previous tile, and frees the
+    // buffers of K(t-1) and V(t-2), which are refilled with K(t+1) and V(t) right away.
     auto swap_barrier = [&](int t) {
         __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
         if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka);
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va);
-    };
-    auto next_offsets = [&](int t) {   // rows of the tiles that swap_barrier(t + 1) will fetch
         if (t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
         if (t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
-    auto phase_barrier = [&]() { __builtin_amdgcn_s_barrier(); };
-    // The matrix block runs at raised wave priority: an MFMA needs one issue slot in eight, and
-    // must not queue behind the other set's dense stream of vector instructions on the same SIMD.
-    auto matrix_phase = [&](bool do_pv, int vbuf, bool do_qk, int kbuf) {
-        __builtin_amdgcn_s_setprio(3);
-        if (do_pv) prefetch_pv(vbuf); else prefetch_qk(kbuf);
-        matrix_block(do_pv, vbuf, do_qk, kbuf);
-        __builtin_amdgcn_s_setprio(0);
-    };
 
-    if (set == 0) {
+    // tile 0: QK and weights only
+    {
         swap_barrier(0);
-        matrix_phase(false, 0, true, 0);
-        phase_barrier();
-        next_offsets(0);
-        softmax_block(0, true);
-        for (int t = 1; t < n_tiles; ++t) {
-            swap_barrier(t);
-            matrix_phase(true, (t - 1) & 1, true, t & 1);
-            phase_barrier();
-            next_offsets(t);
-            softmax_block(t, false);
-        }
+        qk_half(0, 0);
+        qk_half(0, 1);
+        if (DENSE && kBN > p.n_tokens) mask_tail(0);
+        float ls = 0.f;
+        exp_half(0, pwA, ls);
+        exp_half(1, pwA, ls);
+        finish_softmax(pwA, ls);
+    }
+    // tile t >= 1: QK(t), weights(t) and PV(t-1) in one straight-line block; the statement order
+    // below is only a hint, the instruction scheduler interleaves the three streams
+    auto tile_step = [&](int t, uint32_t (&pw_cur)[2][8], const uint32_t (&pw_prev)[2][8]) {
+        swap_barrier(t);
+        float ls = 0.f;
+        qk_half(t & 1, 0);
+        qk_half(t & 1, 1);
+        if (DENSE && (t + 1) * kBN > p.n_tokens) mask_tail(t);
+        exp_half(0, pw_cur, ls);
+        pv_half((t - 1) & 1, 0, pw_prev);
+        exp_half(1, pw_cur, ls);
+        pv_half((t - 1) & 1, 1, pw_prev);
+        finish_softmax(pw_cur, ls);
+    };
+    int t = 1;
+    for (; t + 1 < n_tiles; t += 2) {
+        tile_step(t, pwB, pwA);
+        tile_step(t + 1, pwA, pwB);
+    }
+    if (t < n_tiles) {
+        tile_step(t, pwB, pwA);
         swap_barrier(n_tiles);
-        matrix_phase(true, (n_tiles - 1) & 1, false, 0);
-        phase_barrier();
+        pv_half((n_tiles - 1) & 1, 0, pwB);
+        pv_half((n_tiles - 1) & 1, 1, pwB);
     } else {
-        swap_barrier(0);
-        next_offsets(0);
-        phase_barrier();
-        matrix_phase(false, 0, true, 0);
-        for (int t = 1; t < n_tiles; ++t) {
-            swap_barrier(t);
-            next_offsets(t);
-            softmax_block(t - 1, t == 1);
-            phase_barrier();
-            matrix_phase(true, (t - 1) & 1, true, t & 1);
-        }
         swap_barrier(n_tiles);
-        softmax_block(n_tiles - 1, n_tiles == 1);
-        phase_barrier();
-        matrix_phase(true, (n_tiles - 1) & 1, false, 0);
+        pv_half((n_tiles - 1) & 1, 0, pwA);
+        pv_half((n_tiles - 1) & 1, 1, pwA);
     }
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
