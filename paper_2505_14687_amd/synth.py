@@ -52,6 +52,18 @@ WORKLOADS: Dict[str, Workload] = {
     "video": Workload("video", (30, 48, 80), (2, 8, 8), 1, 24, 128, "bf16", 1005,
                       {"B3": ("block", (1, 1, 1)), "X": ("cross", (0, 0, 0)),
                        "Xplanes": ("cross_planes", (0, 0, 0))}),
+    # --- beyond the five benchmark configs: the paper's own video shape (Sec. 4.2: 32x48x80 latent
+    # tokens, groups 4x8x8) and the group-size / radius ablation of its appendix at 512x512 tokens
+    "video_paper": Workload("video_paper", (32, 48, 80), (4, 8, 8), 1, 24, 128, "bf16", 1006,
+                            {"B3": ("block", (1, 1, 1)), "X": ("cross", (0, 0, 0)),
+                             "Xplanes": ("cross_planes", (0, 0, 0))}),
+    "img8192_g8": Workload("img8192_g8", (512, 512), (8, 8), 1, 24, 128, "bf16", 1007,
+                           {"B3": ("block", (1, 1)), "B5": ("block", (2, 2)), "B7": ("block", (3, 3)),
+                            "X": ("cross", (0, 0))}),
+    "img8192_g32": Workload("img8192_g32", (512, 512), (32, 32), 1, 24, 128, "bf16", 1008,
+                            {"B3": ("block", (1, 1)), "X": ("cross", (0, 0))}),
+    "img8192_b2": Workload("img8192_b2", (512, 512), (16, 16), 1, 24, 128, "bf16", 1004,
+                           {"B5": ("block", (2, 2))}),
 }
 
 

@@ -98,6 +98,22 @@ def test_video_sampled_rows(label):
     print(label, assert_close(gather_rows(O, samples), want, "bf16", f"video {label}"))
 
 
+# ---- beyond the five configs: the paper's video shape and its group-size / radius ablation ------
+@pytest.mark.parametrize("name,label", [
+    ("video_paper", "B3"), ("video_paper", "X"), ("video_paper", "Xplanes"),
+    ("img8192_g8", "B3"), ("img8192_g8", "B7"), ("img8192_g8", "X"),
+    ("img8192_g32", "B3"), ("img8192_g32", "X"),
+])
+def test_paper_shapes_sampled_rows(name, label):
+    w, host, dev = workload_on_device(name)
+    pattern, radius = w.patterns[label]
+    O = run_pattern(w, dev, pattern, radius)
+    samples = synth.sample_rows(2006, 1024, w.batch, w.heads, w.n_tokens)
+    samples[:3, 2] = [0, w.n_tokens - 1, w.n_tokens // 2 + 17]
+    want = orc.grat_attention_rows(*host, samples, w.grid, w.group, pattern, radius, w.scale)
+    print(name, label, assert_close(gather_rows(O, samples), want, "bf16", f"{name} {label}"))
+
+
 # ---- edge shapes ----------------------------------------------------------------------------
 def small_case(B, H, grid, group, pattern, radius, q_gain=1.0, seed=91):
     N = int(np.prod(grid))
