@@ -34,7 +34,10 @@ list counts, the sparsity and farthest-token figures printed in Tab. 1 / Tab. 3 
 per-query brute-force loops, full coverage == dense softmax attention (checked against
 torch's float64 scaled_dot_product_attention), rows of P sum to 1, constant V passes
 through, K == 0 gives the mean of V over the attendable set, group 1x1 == per-token
-window / criss-cross attention, and invariance under a group-major token permutation.
+window / criss-cross attention, and mirror / transpose equivariance.  The joint-sequence
+functions (prompt tokens next to the grid) are pinned by per-query loops, by their reduction
+to the plain functions for n_global = 0 and on the grid block, and by the printed GRAT-X
+sparsities counted from their mask.
 """
 from __future__ import annotations
 
@@ -208,6 +211,62 @@ def grat_attention_rows(Q: np.ndarray, K: np.ndarray, V: np.ndarray, samples: np
         p = np.exp(s - s.max())
         p /= p.sum()
         out[i] = p @ as_f64(V[b, h, keys])
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# Joint sequences: prompt ("global") tokens next to the grid tokens
+# ----------------------------------------------------------------------------------------
+# The method section defines attention over the spatial tokens only; the models it is applied to
+# attend over a joint sequence of prompt tokens and image / video tokens, and the FLOPs
+# sparsities printed for GRAT-X in the ablation table are reproduced only if every image query
+# also attends 512 prompt tokens.  Reading taken here: n_global prompt tokens are stored before
+# (global_first) or after the grid tokens; a grid query attends its attendable groups plus all
+# prompt tokens; a prompt query attends every token.
+def joint_mask_rows(rows: np.ndarray, n_global: int, global_first: bool, grid: Sequence[int],
+                    group: Sequence[int], pattern: str, radius: Sequence[int]) -> np.ndarray:
+    """Boolean [R, n_global + N]: may query row rows[r] of the joint sequence attend row j?"""
+    N = int(np.prod(grid))
+    rows = np.asarray(rows, dtype=np.int64)
+    g0 = 0 if global_first else N              # first prompt row
+    s0 = n_global if global_first else 0       # first grid row
+    is_global_q = (rows >= g0) & (rows < g0 + n_global)
+    mask = np.zeros((len(rows), n_global + N), dtype=bool)
+    mask[:, g0:g0 + n_global] = True           # everyone attends the prompt tokens
+    mask[is_global_q, :] = True                # prompt queries attend everything
+    grid_q = np.nonzero(~is_global_q)[0]
+    if len(grid_q):
+        mask[np.ix_(grid_q, np.arange(s0, s0 + N))] = mask_rows(rows[grid_q] - s0, grid, group, pattern, radius)
+    return mask
+
+
+def joint_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, n_global: int, global_first: bool,
+                    grid: Sequence[int], group: Sequence[int], pattern: str, radius: Sequence[int],
+                    scale: float, row_chunk: int = 512) -> np.ndarray:
+    """All rows of the joint sequence.  Q, K, V [B, H, n_global + N, d] -> O float64."""
+    B, H, L, d = Q.shape
+    assert L == n_global + int(np.prod(grid))
+    O = np.empty((B, H, L, d), dtype=np.float64)
+    for r0 in range(0, L, row_chunk):
+        rows = np.arange(r0, min(L, r0 + row_chunk))
+        mask = joint_mask_rows(rows, n_global, global_first, grid, group, pattern, radius)
+        for b in range(B):
+            for h in range(H):
+                O[b, h, rows] = masked_attention(Q[b, h, rows], K[b, h], V[b, h], mask, scale)
+    return O
+
+
+def joint_attention_rows(Q, K, V, samples: np.ndarray, n_global: int, global_first: bool,
+                         grid: Sequence[int], group: Sequence[int], pattern: str,
+                         radius: Sequence[int], scale: float) -> np.ndarray:
+    """Selected (batch, head, row) triples of the joint sequence -> O float64 [R, d]."""
+    samples = np.asarray(samples, dtype=np.int64)
+    out = np.empty((len(samples), Q.shape[-1]), dtype=np.float64)
+    for i, (b, h, r) in enumerate(samples):
+        keys = np.nonzero(joint_mask_rows(np.array([r]), n_global, global_first, grid, group, pattern, radius)[0])[0]
+        s = (as_f64(K[b, h, keys]) @ as_f64(Q[b, h, r])) * float(scale)
+        p = np.exp(s - s.max())
+        out[i] = (p / p.sum()) @ as_f64(V[b, h, keys])
     return out
 
 

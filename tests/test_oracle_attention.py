@@ -226,3 +226,81 @@ def test_synth_is_seeded_and_per_head():
     assert (synth.head_normal(w.seed, 1, 0, 1, 1024, 64) == K1[0, 1]).all()
     assert abs(float(Q1.std()) - 1.0) < 0.02 and abs(float(V1.mean())) < 0.02
     assert not (Q1[0, 0] == Q1[0, 1]).all() and not (Q1 == K1).all()
+
+
+# -- joint sequences: prompt tokens next to the grid tokens ------------------------------------------
+def brute_joint_attention(Q, K, V, n_global, global_first, grid, group, pattern, radius, scale):
+    """Per-query loops over the joint sequence, written from the reading directly: prompt rows
+    attend everything, grid rows attend the prompt rows plus their attendable groups."""
+    B, H, L, d = Q.shape
+    N = int(np.prod(grid))
+    ndim = len(grid)
+    coords = list(itertools.product(*[range(t) for t in grid]))
+    g0, s0 = (0, n_global) if global_first else (N, 0)
+    out = np.zeros((B, H, L, d))
+    for b in range(B):
+        for h in range(H):
+            for i in range(L):
+                keys = []
+                for j in range(L):
+                    qi_global = g0 <= i < g0 + n_global
+                    kj_global = g0 <= j < g0 + n_global
+                    if qi_global or kj_global:
+                        keys.append(j)
+                        continue
+                    p = [coords[i - s0][k] // group[k] for k in range(ndim)]
+                    m = [coords[j - s0][k] // group[k] for k in range(ndim)]
+                    if pattern == "block":
+                        ok = all(abs(m[k] - p[k]) <= radius[k] for k in range(ndim))
+                    else:
+                        ok = sum(m[k] != p[k] for k in range(ndim)) <= 1
+                    if ok:
+                        keys.append(j)
+                s = np.array([sum(float(Q[b, h, i, c]) * float(K[b, h, j, c]) for c in range(d)) * scale for j in keys])
+                w = np.exp(s - s.max())
+                w /= w.sum()
+                for wj, j in zip(w, keys):
+                    out[b, h, i] += wj * V[b, h, j]
+    return out
+
+
+@pytest.mark.parametrize("n_global,global_first,grid,group,pattern,radius", [
+    (5, True, (6, 8), (2, 2), "block", (1, 1)),
+    (5, False, (6, 8), (2, 2), "block", (1, 1)),
+    (3, True, (6, 8), (2, 4), "cross", (0, 0)),
+    (4, False, (4, 4, 6), (2, 2, 3), "cross", (0, 0, 0)),
+    (1, True, (4, 4, 6), (2, 2, 3), "block", (1, 0, 1)),
+])
+def test_joint_sequence_matches_brute_force(n_global, global_first, grid, group, pattern, radius):
+    L = n_global + int(np.prod(grid))
+    Q, K, V = rand_qkv(31, 1, 2, L, 4, gain=2.0)
+    want = brute_joint_attention(Q, K, V, n_global, global_first, grid, group, pattern, radius, 0.41)
+    got = orc.joint_attention(Q, K, V, n_global, global_first, grid, group, pattern, radius, 0.41, row_chunk=13)
+    np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-12)
+    samples = synth.sample_rows(7, 25, 1, 2, L)
+    rows = orc.joint_attention_rows(Q, K, V, samples, n_global, global_first, grid, group, pattern, radius, 0.41)
+    np.testing.assert_allclose(rows, want[samples[:, 0], samples[:, 1], samples[:, 2]], rtol=1e-11, atol=1e-12)
+
+
+def test_joint_sequence_without_prompt_tokens_is_the_plain_pattern():
+    grid, group = (16, 16), (4, 4)
+    Q, K, V = rand_qkv(37, 1, 2, 256, 8)
+    for gf in (True, False):
+        got = orc.joint_attention(Q, K, V, 0, gf, grid, group, "block", (1, 1), 0.3)
+        np.testing.assert_array_equal(got, orc.grat_attention(Q, K, V, grid, group, "block", (1, 1), 0.3))
+
+
+def test_joint_mask_structure_and_printed_sparsity():
+    from conftest import read_golden_figures
+    fig = read_golden_figures()
+    # small case: structure of the mask
+    m = orc.joint_mask_rows(np.arange(3 + 64), 3, True, (8, 8), (4, 4), "block", (0, 0))
+    assert m[:3].all() and m[:, :3].all()
+    assert (m[3:, 3:] == orc.mask_rows(np.arange(64), (8, 8), (4, 4), "block", (0, 0))).all()
+    m2 = orc.joint_mask_rows(np.arange(3 + 64), 3, False, (8, 8), (4, 4), "block", (0, 0))
+    assert (m2[:64, :64] == m[3:, 3:]).all() and m2[64:].all() and m2[:, 64:].all()
+    # Tab. 6: the fraction of keys an image query of the 512x512 grid skips with 512 prompt tokens
+    for g in (8, 16, 32):
+        row = orc.joint_mask_rows(np.array([512 + 12345]), 512, True, (512, 512), (g, g), "cross", (0, 0))[0]
+        sparsity = 100.0 * (1.0 - row.sum() / row.size)
+        assert abs(sparsity - fig[f"sparsity_gratx_{g}"]) < 0.0075
