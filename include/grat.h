@@ -122,6 +122,25 @@ grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void
                                int32_t max_kv, void* hip_stream);
 
 /*
+ * The same for a JOINT sequence of prompt tokens and grid tokens, as the diffusion transformers the
+ * method is applied to use (the method section, Sec. 3.2, defines the spatial part only; the
+ * sparsities printed in its ablation table count 512 always-attended prompt tokens).
+ *   n_global      >= 0 prompt ("global") tokens; the sequence has n_global + prod grid[k] rows
+ *   global_first  non-zero: the prompt tokens are rows [0, n_global) and the grid tokens follow;
+ *                 zero: the grid tokens come first
+ * A grid query attends the KV groups of its list plus every prompt token; a prompt query attends
+ * the whole sequence.  Everything else as in grat_attention_fwd (which is the n_global = 0 case).
+ * Supported: GRAT_BF16 (GRAT_F32 only with n_global = 0).
+ */
+grat_status grat_attention_global_fwd(const void* Q, const void* K, const void* V, void* O,
+                                      grat_dtype dtype, int32_t batch, int32_t heads,
+                                      int32_t head_dim, int64_t stride_b, int64_t stride_h,
+                                      int64_t stride_n, float scale, int32_t n_global,
+                                      int32_t global_first, int32_t ndim, const int32_t* grid,
+                                      const int32_t* group, const int32_t* d_kv_count,
+                                      const int32_t* d_kv_index, int32_t max_kv, void* hip_stream);
+
+/*
  * Full attention (Sec. 3.1, Eq. 1) over n_tokens tokens with the same tiling and arithmetic as
  * grat_attention_fwd: the comparison point for speedups.  Any n_tokens >= 1.
  * Supported dtypes / head_dim as above.

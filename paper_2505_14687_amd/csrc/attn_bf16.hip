@@ -81,7 +81,15 @@ __device__ __forceinline__ float sum_across_halves(float x) {
     return lo + hi;
 }
 
-template <int NWAVES, bool DENSE>
+// MODE: what a workgroup can be.
+//   kGrouped  every workgroup is a query tile of one group and walks that group's KV list;
+//   kDense    every workgroup is a tile of consecutive query rows and walks all KV tiles;
+//   kJoint    joint sequence of prompt tokens and grid tokens: the first p.n_dense_tiles tiles are
+//             dense tiles over the prompt rows (they attend the whole sequence), the others are
+//             grouped tiles whose walk starts with the prompt tokens' KV tiles.
+enum : int { kGrouped = 0, kDense = 1, kJoint = 2 };
+
+template <int NWAVES, int MODE>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
     constexpr int NT = NWAVES * 64;
     constexpr int BM = NWAVES * 32;
@@ -97,11 +105,29 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     const int qcol = lane & 31;   // query within the wave's 32
     const int half = lane >> 5;
 
-    const int tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
-    if (tile >= p.total_tiles) return;
-
     const Geometry& geo = p.geo;
-    const int tiles_per_head = DENSE ? p.q_tiles : geo.num_groups * p.q_tiles;
+    int tile;             // index among the tiles of its kind
+    bool dense;           // wave-uniform: this workgroup is a dense tile
+    if (MODE == kJoint) {
+        // The long-running dense tiles get the lowest block indices, dealt round-robin over the
+        // XCDs; behind them every XCD walks its contiguous range of grouped tiles.
+        const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
+        const int dense_per_xcd = (p.n_dense_tiles + kNumXcd - 1) / kNumXcd;
+        dense = idx < dense_per_xcd;
+        if (dense) {
+            tile = idx * kNumXcd + xcd;
+            if (tile >= p.n_dense_tiles) return;
+        } else {
+            const int per = (p.total_tiles + kNumXcd - 1) / kNumXcd;
+            tile = xcd * per + (idx - dense_per_xcd);
+            if (idx - dense_per_xcd >= per || tile >= p.total_tiles) return;
+        }
+    } else {
+        dense = MODE == kDense;
+        tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
+        if (tile >= p.total_tiles) return;
+    }
+    const int tiles_per_head = dense ? p.q_tiles_dense : geo.num_groups * p.q_tiles;
     const int bh = tile / tiles_per_head;
     const int t_in_head = tile % tiles_per_head;
     const int64_t head_off = (int64_t)(bh / p.heads) * p.stride_b + (int64_t)(bh % p.heads) * p.stride_h;
@@ -114,37 +140,46 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // byte offsets (row * stride_n * 2): s_rowbytes[t] of intra-group token t relative to its group's
     // first token, s_origin[i] of the first token of the i-th listed KV group
     uint32_t* s_rowbytes = (uint32_t*)s_dyn;
-    uint32_t* s_origin = (uint32_t*)s_dyn + (DENSE ? 0 : geo.group_tokens);
+    uint32_t* s_origin = (uint32_t*)s_dyn + (MODE == kDense ? 0 : geo.group_tokens);
     const uint32_t row_pitch = (uint32_t)stride_n * 2u;   // bytes between consecutive tokens
 
     int n_tiles;        // KV tiles to walk
     int tiles_per_group = 1;
+    int n_lead = 0;     // grouped tile of a joint sequence: leading KV tiles that hold the prompt tokens
+    int mask_tile = -1, mask_valid = kBN;   // the one KV tile with fewer than 64 valid keys, if any
     int q_row;          // token row of this lane's query
     bool q_valid = true;
-    if (DENSE) {
+    if (dense) {
         n_tiles = (p.n_tokens + kBN - 1) / kBN;
-        q_row = t_in_head * BM + wave * 32 + qcol;
-        q_valid = q_row < p.n_tokens;
-        if (!q_valid) q_row = p.n_tokens - 1;
+        if (p.n_tokens % kBN) { mask_tile = n_tiles - 1; mask_valid = p.n_tokens % kBN; }
+        const int r = t_in_head * BM + wave * 32 + qcol;   // row among the dense query rows
+        q_valid = r < p.n_dense_rows;
+        q_row = p.dense_row0 + (q_valid ? r : p.n_dense_rows - 1);
     } else {
         const int gamma = strip_order_group(t_in_head / p.q_tiles, geo.G[0] * geo.G[1], geo.G[2], p.strip_w);
         const int qt = t_in_head % p.q_tiles;
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];
+        const uint32_t grid_base = MODE == kJoint ? (uint32_t)p.grid_row0 * row_pitch : 0u;
         for (int t = tid; t < n_g; t += NT)
             s_rowbytes[t] = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
         const int cnt = p.kv_count[gamma];
         for (int i = tid; i < cnt; i += NT) {
             const int gid = p.kv_index[(int64_t)gamma * p.max_kv + i];
-            s_origin[i] = (uint32_t)((gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
+            s_origin[i] = grid_base +
+                          (uint32_t)((gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                                      (gid % geo.G[2]) * geo.g[2]) * row_pitch;
         }
         __syncthreads();
         tiles_per_group = n_g / kBN;
-        n_tiles = cnt * tiles_per_group;
+        if (MODE == kJoint) {
+            n_lead = (p.n_global + kBN - 1) / kBN;
+            if (p.n_global % kBN) { mask_tile = n_lead - 1; mask_valid = p.n_global % kBN; }
+        }
+        n_tiles = n_lead + cnt * tiles_per_group;
         const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                              (gamma % geo.G[2]) * geo.g[2];
-        q_row = q_origin + (int)(s_rowbytes[qt * BM + wave * 32 + qcol] / row_pitch);
+        q_row = (MODE == kJoint ? p.grid_row0 : 0) + q_origin + (int)(s_rowbytes[qt * BM + wave * 32 + qcol] / row_pitch);
     }
     if (n_tiles == 0) return;   // an empty list is outside the contract; never touch memory for it
 
@@ -196,11 +231,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // Offsets of a tile are looked up one tile before it is fetched, so the table reads never sit
     // between a barrier and the loads that follow it.
     auto tile_addr = [&](TileAddr& a, const uint32_t* col, int t, int& gi, int& j) {
-        if (DENSE) {
-            a.base = (uint32_t)(t * kBN) * row_pitch;
+        if (MODE != kGrouped && (dense || t < n_lead)) {
+            // consecutive rows: the whole sequence (dense tile) or the prompt tokens (leading tiles)
+            const int first = dense ? 0 : p.global_row0, count = dense ? p.n_tokens : p.n_global;
+            a.base = (uint32_t)(first + t * kBN) * row_pitch;
 #pragma unroll
             for (int k = 0; k < LPW; ++k)   // rows past the end re-read the last token (masked later)
-                a.off[k] = (uint32_t)min(load_row[k], p.n_tokens - 1 - t * kBN) * row_pitch + col[k];
+                a.off[k] = (uint32_t)min(load_row[k], count - 1 - t * kBN) * row_pitch + col[k];
         } else {
             a.base = __builtin_amdgcn_readfirstlane(s_origin[gi]);
 #pragma unroll
@@ -292,13 +329,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, ls, false);
         }
     };
-    auto mask_tail = [&](int t) {   // dense path: keys past the end of the sequence get weight 0
+    auto mask_tail = [&]() {   // the ragged tile: keys past the end of their run get weight 0
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int key = t * kBN + 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (key >= p.n_tokens) S[kb][r] = -INFINITY;
+                const int key = 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (key >= mask_valid) S[kb][r] = -INFINITY;
             }
     };
     // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to be:
@@ -353,7 +390,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         swap_barrier(0);
         qk_half(0, 0);
         qk_half(0, 1);
-        if (DENSE && kBN > p.n_tokens) mask_tail(0);
+        if (MODE != kGrouped && mask_tile == 0) mask_tail();
         float ls = 0.f;
         exp_half(0, pwA, ls);
         exp_half(1, pwA, ls);
@@ -366,7 +403,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         float ls = 0.f;
         qk_half(t & 1, 0);
         qk_half(t & 1, 1);
-        if (DENSE && (t + 1) * kBN > p.n_tokens) mask_tail(t);
+        if (MODE != kGrouped && t == mask_tile) mask_tail();
         exp_half(0, pw_cur, ls);
         pv_half((t - 1) & 1, 0, pw_prev);
         exp_half(1, pw_cur, ls);
@@ -406,20 +443,27 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 }
 
 template <int NWAVES>
-static hipError_t launch_one(const AttnParams& p, bool dense, hipStream_t stream) {
-    const dim3 grid(xcd_padded_blocks(p.total_tiles)), block(NWAVES * 64);
-    const size_t dyn = dense ? 0 : sizeof(int32_t) * ((size_t)p.geo.group_tokens + p.max_kv);
-    if (dense) hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, true>), grid, block, dyn, stream, p);
-    else       hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, false>), grid, block, dyn, stream, p);
+static hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
+    const dim3 block(NWAVES * 64);
+    const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * ((size_t)p.geo.group_tokens + p.max_kv);
+    if (mode == kDense) {
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+    } else if (mode == kGrouped) {
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+    } else {
+        const int blocks = xcd_padded_blocks(p.n_dense_tiles) + xcd_padded_blocks(p.total_tiles);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kJoint>), dim3(blocks), block, dyn, stream, p);
+    }
     return hipGetLastError();
 }
 
-// p.q_tiles was computed by the host for the query-tile height chosen here: 256, 128 or 64 rows.
-hipError_t launch_attn_bf16(const AttnParams& p, bool dense, hipStream_t stream) {
-    const int bm = dense ? 256 : (p.geo.group_tokens / p.q_tiles);
-    if (bm == 256) return launch_one<8>(p, dense, stream);
-    if (bm == 128) return launch_one<4>(p, dense, stream);
-    return launch_one<2>(p, dense, stream);
+// The host computed p.q_tiles (and p.q_tiles_dense) for the query-tile height chosen here:
+// 256, 128 or 64 rows.
+hipError_t launch_attn_bf16(const AttnParams& p, int mode, hipStream_t stream) {
+    const int bm = mode == kDense ? 256 : (p.geo.group_tokens / p.q_tiles);
+    if (bm == 256) return launch_one<8>(p, mode, stream);
+    if (bm == 128) return launch_one<4>(p, mode, stream);
+    return launch_one<2>(p, mode, stream);
 }
 
 }  // namespace grat

@@ -134,24 +134,29 @@ extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid,
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }
 
-extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void* O,
-                                          grat_dtype dtype, int32_t batch, int32_t heads,
-                                          int32_t head_dim, int64_t stride_b, int64_t stride_h,
-                                          int64_t stride_n, float scale, int32_t ndim,
-                                          const int32_t* grid, const int32_t* group,
-                                          const int32_t* d_kv_count, const int32_t* d_kv_index,
-                                          int32_t max_kv, void* hip_stream) {
+// Shared by grat_attention_fwd (n_global = 0) and grat_attention_global_fwd.
+static grat_status attention_fwd(const void* Q, const void* K, const void* V, void* O,
+                                 grat_dtype dtype, int32_t batch, int32_t heads, int32_t head_dim,
+                                 int64_t stride_b, int64_t stride_h, int64_t stride_n, float scale,
+                                 int32_t n_global, int32_t global_first, int32_t ndim,
+                                 const int32_t* grid, const int32_t* group,
+                                 const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                 int32_t max_kv, void* hip_stream) {
     if (!d_kv_count || !d_kv_index) return GRAT_ERR_NULL;
     Geometry geo;
     grat_status st = make_geometry(ndim, grid, group, &geo);
     if (st != GRAT_OK) return st;
-    st = check_tensors(Q, K, V, O, dtype, batch, heads, head_dim, geo.n_tokens, stride_b, stride_h,
+    if (n_global < 0) return GRAT_ERR_BAD_DIMS;
+    const int64_t seq_len = geo.n_tokens + n_global;
+    if (seq_len >= kMaxElems) return GRAT_ERR_BAD_DIMS;
+    st = check_tensors(Q, K, V, O, dtype, batch, heads, head_dim, seq_len, stride_b, stride_h,
                        stride_n, scale);
     if (st != GRAT_OK) return st;
     for (int k = 0; k < 3; ++k)
         if (geo.T[k] % geo.g[k]) return GRAT_ERR_INDIVISIBLE;
     if (max_kv < 1) return GRAT_ERR_BUFFER_TOO_SMALL;
     if (max_kv > kMaxListLen) return GRAT_ERR_UNSUPPORTED;
+    if (n_global > 0 && dtype != GRAT_BF16) return GRAT_ERR_UNSUPPORTED;
 
     AttnParams p{};
     p.Q = Q; p.K = K; p.V = V; p.O = O;
@@ -160,7 +165,7 @@ extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const vo
     p.scale_log2 = scale * 1.4426950408889634f;
     p.geo = geo;
     p.kv_count = d_kv_count; p.kv_index = d_kv_index; p.max_kv = max_kv;
-    p.n_tokens = (int32_t)geo.n_tokens;
+    p.n_tokens = (int32_t)seq_len;
 
     const int n_g = geo.group_tokens;
     int bm;   // query rows per workgroup
@@ -177,10 +182,45 @@ extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const vo
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
+    int mode = 0;
+    if (n_global > 0) {   // joint sequence: prompt rows become dense tiles launched ahead of the rest
+        mode = 2;
+        p.n_global = n_global;
+        p.global_row0 = global_first ? 0 : (int32_t)geo.n_tokens;
+        p.grid_row0 = global_first ? n_global : 0;
+        p.n_dense_rows = n_global;
+        p.dense_row0 = p.global_row0;
+        p.q_tiles_dense = (n_global + bm - 1) / bm;
+        p.n_dense_tiles = batch * heads * p.q_tiles_dense;
+    }
     const hipError_t e = dtype == GRAT_BF16
-                             ? launch_attn_bf16(p, false, (hipStream_t)hip_stream)
+                             ? launch_attn_bf16(p, mode, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, false, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
+}
+
+extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void* O,
+                                          grat_dtype dtype, int32_t batch, int32_t heads,
+                                          int32_t head_dim, int64_t stride_b, int64_t stride_h,
+                                          int64_t stride_n, float scale, int32_t ndim,
+                                          const int32_t* grid, const int32_t* group,
+                                          const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                          int32_t max_kv, void* hip_stream) {
+    return attention_fwd(Q, K, V, O, dtype, batch, heads, head_dim, stride_b, stride_h, stride_n,
+                         scale, 0, 1, ndim, grid, group, d_kv_count, d_kv_index, max_kv, hip_stream);
+}
+
+extern "C" grat_status grat_attention_global_fwd(const void* Q, const void* K, const void* V, void* O,
+                                                 grat_dtype dtype, int32_t batch, int32_t heads,
+                                                 int32_t head_dim, int64_t stride_b, int64_t stride_h,
+                                                 int64_t stride_n, float scale, int32_t n_global,
+                                                 int32_t global_first, int32_t ndim,
+                                                 const int32_t* grid, const int32_t* group,
+                                                 const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                                 int32_t max_kv, void* hip_stream) {
+    return attention_fwd(Q, K, V, O, dtype, batch, heads, head_dim, stride_b, stride_h, stride_n,
+                         scale, n_global, global_first, ndim, grid, group, d_kv_count, d_kv_index,
+                         max_kv, hip_stream);
 }
 
 extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, const void* V, void* O,
@@ -201,12 +241,15 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     p.n_tokens = (int32_t)n_tokens;
     const int bm = dtype == GRAT_BF16 ? 256 : 64;
     p.q_tiles = (int32_t)((n_tokens + bm - 1) / bm);
+    p.q_tiles_dense = p.q_tiles;
+    p.n_dense_rows = (int32_t)n_tokens;
+    p.dense_row0 = 0;
     const int64_t total = (int64_t)batch * heads * p.q_tiles;
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
     const hipError_t e = dtype == GRAT_BF16
-                             ? launch_attn_bf16(p, true, (hipStream_t)hip_stream)
+                             ? launch_attn_bf16(p, 1, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, true, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }

@@ -30,10 +30,19 @@ struct AttnParams {
     const int32_t* kv_count;
     const int32_t* kv_index;
     int32_t max_kv;
-    int32_t n_tokens;          // dense path: sequence length
-    int32_t q_tiles;           // query tiles per group (grouped) or per head (dense)
-    int32_t total_tiles;       // batch * heads * (groups *) q_tiles
+    int32_t n_tokens;          // dense tiles: number of KV rows (the whole sequence)
+    int32_t q_tiles;           // query tiles per group
+    int32_t total_tiles;       // batch * heads * groups * q_tiles (grouped) or batch * heads * q_tiles_dense (dense)
     int32_t strip_w;           // grouped bf16 path: query groups are walked in column strips this wide
+    // dense tiles (dense entry point, and the prompt rows of a joint sequence)
+    int32_t q_tiles_dense;     // query tiles per head
+    int32_t n_dense_rows;      // query rows per head
+    int32_t dense_row0;        // first of them
+    int32_t n_dense_tiles;     // joint sequence: batch * heads * q_tiles_dense, launched ahead of the grouped tiles
+    // joint sequence (prompt tokens + grid tokens)
+    int32_t n_global;          // prompt tokens
+    int32_t global_row0;       // first prompt row
+    int32_t grid_row0;         // first grid row
 };
 
 // Launchers: each returns the hipError_t of its launch.
@@ -41,7 +50,7 @@ hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern 
                                     const int32_t radius[3], int32_t* d_kv_count,
                                     int32_t* d_kv_index, int32_t max_kv, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, bool dense, hipStream_t stream);
-hipError_t launch_attn_bf16(const AttnParams& p, bool dense, hipStream_t stream);
+hipError_t launch_attn_bf16(const AttnParams& p, int mode, hipStream_t stream);   // mode: 0 grouped, 1 dense, 2 joint
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
 // contiguous range of the logical tile order instead, so that tiles sharing K/V meet in one L2.

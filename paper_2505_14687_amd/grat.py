@@ -18,7 +18,7 @@ GRAT_OK = 0
 PATTERNS = {"block": 0, "cross": 1, "cross_planes": 2, "dense": 3}
 DTYPES = {torch.bfloat16: 0, torch.float32: 1}
 EXPORTS = ("grat_block_list_shape", "grat_build_block_lists", "grat_attention_fwd",
-           "grat_dense_attention_fwd", "grat_status_string")
+           "grat_attention_global_fwd", "grat_dense_attention_fwd", "grat_status_string")
 
 _i32, _i64, _f32, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
 _pi32 = ctypes.POINTER(ctypes.c_int32)
@@ -47,6 +47,10 @@ def lib() -> ctypes.CDLL:
         L.grat_attention_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i64, _i64,
                                          _f32, _i32, _pi32, _pi32, _vp, _vp, _i32, _vp]
         L.grat_attention_fwd.restype = _i32
+        L.grat_attention_global_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i64, _i64,
+                                                _i64, _f32, _i32, _i32, _i32, _pi32, _pi32, _vp, _vp,
+                                                _i32, _vp]
+        L.grat_attention_global_fwd.restype = _i32
         L.grat_dense_attention_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i64, _i32,
                                                _i64, _i64, _i64, _f32, _vp]
         L.grat_dense_attention_fwd.restype = _i32
@@ -125,6 +129,24 @@ def grat_attention_fwd(Q, K, V, scale: float, grid: Sequence[int], group: Sequen
                                   _stream_ptr(stream))
     if st != GRAT_OK:
         raise GratError(st, "grat_attention_fwd")
+    return O
+
+
+def grat_attention_global_fwd(Q, K, V, scale: float, n_global: int, global_first: bool,
+                              grid: Sequence[int], group: Sequence[int], kv_count, kv_index,
+                              out=None, stream=None):
+    """Joint sequence of n_global prompt tokens and the grid tokens; Q, K, V: [B, H, n_global + N, d]."""
+    O = torch.empty_like(Q) if out is None else out
+    _check_qkvo(Q, K, V, O)
+    B, H, L, d = Q.shape
+    st = lib().grat_attention_global_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                         DTYPES[Q.dtype], B, H, d, Q.stride(0), Q.stride(1),
+                                         Q.stride(2), float(scale), int(n_global), int(bool(global_first)),
+                                         len(grid), _ivec(grid), _ivec(group), kv_count.data_ptr(),
+                                         kv_index.data_ptr(), int(kv_index.shape[1]),
+                                         _stream_ptr(stream))
+    if st != GRAT_OK:
+        raise GratError(st, "grat_attention_global_fwd")
     return O
 
 

@@ -98,3 +98,16 @@ def test_binding_rejects_host_tensors():
     x = torch.zeros(1, 1, 64, 128, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         grat.grat_dense_attention_fwd(x, x, x, 0.1, out=torch.zeros_like(x))
+
+
+def test_joint_sequence_argument_errors():
+    L = grat.lib()
+    i32x2 = ctypes.c_int32 * 2
+    fake = 0x1000
+    def call(dtype=0, n_global=512, sn=128, grid=(64, 64)):
+        return L.grat_attention_global_fwd(fake, fake, fake, fake, dtype, 1, 2, 128, 0, (4096 + 512) * 128, sn,
+                                           0.1, n_global, 1, 2, i32x2(*grid), i32x2(16, 16), fake, fake, 9, None)
+    assert call(n_global=-1) == 2
+    assert call(dtype=1) == 6                      # prompt tokens on the fp32 path
+    assert call(grid=(64, 60)) == 3
+    assert call(grid=(1 << 15, 1 << 15)) in (2, 6)
