@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-others", action="store_true", help="skip the workload's other patterns")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--n-global", type=int, default=0,
+                    help="prompt tokens ahead of the grid tokens (joint sequence, grat_attention_global_fwd)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures one GPU only (heads shard across GPUs with no "
@@ -64,7 +66,9 @@ def main():
     n_g = int(np.prod(w.group))
 
     t0 = time.time()
-    host = synth.make_workload_qkv(w, threads=16)
+    n_glob = args.n_global
+    n_seq = n_glob + w.n_tokens
+    host = synth.make_qkv(w.batch, w.heads, n_seq, w.head_dim, w.dtype, w.seed, threads=16)
     def dev(x):
         if x.dtype == np.uint16:
             return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
@@ -78,8 +82,15 @@ def main():
     log(f"inputs: {args.workload} {tuple(Q.shape)} {w.dtype} generated+uploaded in {time.time() - t0:.1f}s")
 
     def flops_of(kv_count):
-        pairs = int(kv_count.sum().item()) * n_g * n_g
+        # grid query: its groups' tokens + every prompt token; prompt query: the whole sequence
+        pairs = int(kv_count.sum().item()) * n_g * n_g + n_glob * w.n_tokens + n_glob * n_seq
         return 4.0 * w.head_dim * w.heads * w.batch * pairs, pairs
+
+    def attention(count, index):
+        if n_glob:
+            grat.grat_attention_global_fwd(Q, K, V, w.scale, n_glob, True, w.grid, w.group, count, index, out=O)
+        else:
+            grat.grat_attention_fwd(Q, K, V, w.scale, w.grid, w.group, count, index, out=O)
 
     def step(pat, rad):
         count, index = grat.grat_build_block_lists(w.grid, w.group, pat, rad)
@@ -90,14 +101,14 @@ def main():
         launch of every timed step is also bracketed by events on the launch stream."""
         for _ in range(warmup):
             count, index = step(pat, rad)
-            grat.grat_attention_fwd(Q, K, V, w.scale, w.grid, w.group, count, index, out=O)
+            attention(count, index)
         torch.cuda.synchronize()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         t0 = time.perf_counter()
         for i in range(steps):
             count, index = step(pat, rad)
             evs[i][0].record()
-            grat.grat_attention_fwd(Q, K, V, w.scale, w.grid, w.group, count, index, out=O)
+            attention(count, index)
             evs[i][1].record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
@@ -136,7 +147,7 @@ def main():
         b.record()
         torch.cuda.synchronize()
         d_ms = a.elapsed_time(b) / reps
-        d_fl = 4.0 * w.head_dim * w.heads * w.batch * float(w.n_tokens) ** 2
+        d_fl = 4.0 * w.head_dim * w.heads * w.batch * float(n_seq) ** 2
         dense = {"kernel_ms": round(d_ms, 3), "tflops": round(d_fl / (d_ms * 1e-3) / 1e12, 2)}
         log(f"dense: {dense}")
 
@@ -146,15 +157,19 @@ def main():
         from oracle import grat_oracle as orc
         # recompute the main pattern's output for the parity sample
         count, index = step(pattern, radius)
-        grat.grat_attention_fwd(Q, K, V, w.scale, w.grid, w.group, count, index, out=O)
+        attention(count, index)
         torch.cuda.synchronize()
         proc = psutil.Process()
-        samples = synth.sample_rows(w.seed + 1000, 4096, w.batch, w.heads, w.n_tokens)
+        samples = synth.sample_rows(w.seed + 1000, 4096, w.batch, w.heads, n_seq)
         done, rows_out, t_cpu0, t0 = 0, [], sum(proc.cpu_times()[:2]), time.perf_counter()
         chunk = 32
         while done < len(samples) and time.perf_counter() - t0 < args.cpu_seconds:
-            rows_out.append(orc.grat_attention_rows(*host, samples[done:done + chunk], w.grid, w.group,
-                                                    pattern, radius, w.scale))
+            if n_glob:
+                rows_out.append(orc.joint_attention_rows(*host, samples[done:done + chunk], n_glob, True,
+                                                         w.grid, w.group, pattern, radius, w.scale))
+            else:
+                rows_out.append(orc.grat_attention_rows(*host, samples[done:done + chunk], w.grid, w.group,
+                                                        pattern, radius, w.scale))
             done += chunk
         wall = time.perf_counter() - t0
         cores = max(1, round((sum(proc.cpu_times()[:2]) - t_cpu0) / wall))
@@ -162,11 +177,15 @@ def main():
         want = np.concatenate(rows_out)[:done]
         s = torch.from_numpy(samples[:done]).cuda()
         got = O[s[:, 0], s[:, 1], s[:, 2]].double().cpu().numpy()
-        keys = orc.mask_rows(samples[:done, 2], w.grid, w.group, pattern, radius).sum(1) if w.n_tokens <= 1 << 16 else None
-        if keys is None:
-            pk = orc.token_group_coords(np.arange(w.n_tokens), w.grid, w.group)
-            pq = orc.token_group_coords(samples[:done, 2], w.grid, w.group)
-            keys = np.array([int(orc.attendable(pq[i], pk, pattern, radius).sum()) for i in range(done)])
+        pk = orc.token_group_coords(np.arange(w.n_tokens), w.grid, w.group)
+        keys = np.empty(done)
+        for i in range(done):
+            row = int(samples[i, 2]) - n_glob
+            if row < 0:
+                keys[i] = n_seq
+            else:
+                pq = orc.token_group_coords(np.array([row]), w.grid, w.group)[0]
+                keys[i] = n_glob + int(orc.attendable(pq, pk, pattern, radius).sum())
         cpu_flops = 4.0 * w.head_dim * float(keys.sum())
         diff = got - want
         cpu = {"value": cpu_flops / wall / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
@@ -184,13 +203,14 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: token grid {'x'.join(map(str, w.grid))}, groups "
                                f"{'x'.join(map(str, w.group))}, batch {w.batch}, {w.heads} heads, head_dim "
-                               f"{w.head_dim}, {w.dtype}, pattern {args.pattern} ({pattern}, radius {list(radius)})",
+                               f"{w.head_dim}, {w.dtype}, pattern {args.pattern} ({pattern}, radius {list(radius)})"
+                               + (f", {n_glob} prompt tokens ahead of the grid tokens" if n_glob else ""),
                    "attended_pairs_per_head": main_r["pairs"], "seed": w.seed,
-                   "step": "grat_build_block_lists + grat_attention_fwd"},
+                   "step": "grat_build_block_lists + " + ("grat_attention_global_fwd" if n_glob else "grat_attention_fwd")},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
-                     "traffic": measured_traffic(args.workload, args.pattern),
-                     "kernel": "grat::attn_bf16_kernel<8, false>",
+                     "traffic": None if n_glob else measured_traffic(args.workload, args.pattern),
+                     "kernel": "grat::attn_bf16_kernel (grouped mode%s)" % (" + prompt tokens" if n_glob else ""),
                      "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4)},
         "cpu_baseline": cpu,
         "dense": dense,
