@@ -145,16 +145,17 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 
     int n_tiles;        // KV tiles to walk
     int tiles_per_group = 1;
+    int n_listed = 1;   // grouped tiles: entries in s_origin
     int n_lead = 0;     // grouped tile of a joint sequence: leading KV tiles that hold the prompt tokens
     int mask_tile = -1, mask_valid = kBN;   // the one KV tile with fewer than 64 valid keys, if any
-    int q_row;          // token row of this lane's query
-    bool q_valid = true;
+    // query rows of this wave: row i of its 32 is row q_first + i of the dense rows, resp. token
+    // q_first + i of its group, whose first token lies q_base bytes into the head
+    uint32_t q_base = 0;
+    int q_first;
     if (dense) {
         n_tiles = (p.n_tokens + kBN - 1) / kBN;
         if (p.n_tokens % kBN) { mask_tile = n_tiles - 1; mask_valid = p.n_tokens % kBN; }
-        const int r = t_in_head * BM + wave * 32 + qcol;   // row among the dense query rows
-        q_valid = r < p.n_dense_rows;
-        q_row = p.dense_row0 + (q_valid ? r : p.n_dense_rows - 1);
+        q_first = t_in_head * BM + wave * 32;
     } else {
         const int gamma = strip_order_group(t_in_head / p.q_tiles, geo.G[0] * geo.G[1], geo.G[2], p.strip_w);
         const int qt = t_in_head % p.q_tiles;
@@ -177,18 +178,26 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             if (p.n_global % kBN) { mask_tile = n_lead - 1; mask_valid = p.n_global % kBN; }
         }
         n_tiles = n_lead + cnt * tiles_per_group;
+        n_listed = cnt;
         const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                              (gamma % geo.G[2]) * geo.g[2];
-        q_row = (MODE == kJoint ? p.grid_row0 : 0) + q_origin + (int)(s_rowbytes[qt * BM + wave * 32 + qcol] / row_pitch);
+        q_base = (uint32_t)((MODE == kJoint ? p.grid_row0 : 0) + q_origin) * row_pitch;
+        q_first = qt * BM + wave * 32;
     }
     if (n_tiles == 0) return;   // an empty list is outside the contract; never touch memory for it
+    // byte offset inside the head of row i of this wave's 32 query (= output) rows; the rows of a
+    // dense tile past the last query re-read the last one and are never stored
+    auto q_row_off = [&](int i) -> uint32_t {
+        if (dense) return (uint32_t)(p.dense_row0 + min(q_first + i, p.n_dense_rows - 1)) * row_pitch;
+        return q_base + s_rowbytes[q_first + i];
+    };
 
     // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
     bf16x8 qf[kD / 16];
     {
-        const uint16_t* src = Qh + (uint32_t)q_row * stride_n + 8 * half;
+        const uint8_t* src = (const uint8_t*)Qh + q_row_off(qcol) + 16 * half;
 #pragma unroll
-        for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 16 * ks);
+        for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
     }
 
     f32x16 oacc[kD / 32];                 // O^T accumulator: 4 blocks of 32 head dims
@@ -239,7 +248,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             for (int k = 0; k < LPW; ++k)   // rows past the end re-read the last token (masked later)
                 a.off[k] = (uint32_t)min(load_row[k], count - 1 - t * kBN) * row_pitch + col[k];
         } else {
-            a.base = __builtin_amdgcn_readfirstlane(s_origin[gi]);
+            a.base = __builtin_amdgcn_readfirstlane(s_origin[min(gi, n_listed - 1)]);   // (may be asked past the end)
 #pragma unroll
             for (int k = 0; k < LPW; ++k) a.off[k] = s_rowbytes[j * kBN + load_row[k]] + col[k];
             if (++j == tiles_per_group) { j = 0; ++gi; }
@@ -250,7 +259,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // the prefetch before the first fragment read that follows.  Completion is waited for
     // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
     auto issue_tile = [&](const uint16_t* head, uint8_t* dst_tile, const TileAddr& a) {
-        const uint8_t* base = (const uint8_t*)head + a.base;
+        // (made uniform again here: carried across iterations the offset may sit in a vector register)
+        const uint8_t* base = (const uint8_t*)head + __builtin_amdgcn_readfirstlane(a.base);
 #pragma unroll
         for (int k = 0; k < LPW; ++k) {
             // LDS destination of this wave's piece; the hardware adds lane * 16
@@ -368,6 +378,20 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         l_run += ls;
     };
 
+    // First tile: there is no older reference, so the maximum is taken up front.
+    auto first_softmax = [&](uint32_t (&pw)[2][8]) {
+        float mx = S[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
+        m_ref = max_across_halves(mx);
+        float ls = 0.f;
+        exp_half(0, pw, ls);
+        exp_half(1, pw, ls);
+        l_run = ls;
+    };
+
     // ---- prologue: K tile 0 -----------------------------------------------------------------
     tile_addr(ka, load_kcol, 0, gi_k, j_k);
     issue_tile(Kh, sK[0], ka);
@@ -381,8 +405,10 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
         if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka);
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va);
-        if (t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
-        if (t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
+        // (grouped: looked up unconditionally, so that the table reads stay inside the straight-line
+        // block that follows instead of becoming a block of their own with its own waits)
+        if (MODE == kGrouped || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
+        if (MODE == kGrouped || t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
 
     // tile 0: QK and weights only
@@ -391,10 +417,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         qk_half(0, 0);
         qk_half(0, 1);
         if (MODE != kGrouped && mask_tile == 0) mask_tail();
-        float ls = 0.f;
-        exp_half(0, pwA, ls);
-        exp_half(1, pwA, ls);
-        finish_softmax(pwA, ls);
+        first_softmax(pwA);
     }
     // tile t >= 1: QK(t), weights(t) and PV(t-1) in one straight-line block; the statement order
     // below is only a hint, the instruction scheduler interleaves the three streams
@@ -427,18 +450,47 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     }
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
+    // In the accumulator layout a lane holds 4 consecutive head dims (8 bytes) at a time of ITS
+    // query; stored like that every store instruction would touch 64 different rows.  So each wave
+    // turns its 32 x 128 output tile through 4 KiB of LDS, 64 head dims at a time: lanes write
+    // their 8-byte pieces, then read back 16-byte chunks as (row = 8*i + lane/8, chunk = lane%8)
+    // and store 8 rows x 128 contiguous bytes per instruction.  The K buffers are free by now (last
+    // read before the final barrier, nothing in flight); a wave only touches its own 4 KiB, so
+    // the only ordering needed is between its own LDS writes and reads.
     const float inv = 1.f / sum_across_halves(l_run);
-    if (q_valid) {
-        uint16_t* dst = Oh + (uint32_t)q_row * stride_n + 4 * half;
+    {
+        uint8_t* stage = &sK[0][0] + wave * 4096;   // [32 rows][8 chunks of 16 B], chunk ^= row & 7
+        const int srow = lane >> 3, schunk = lane & 7;
+        uint32_t st_off[4];
+        bool st_ok[4];
 #pragma unroll
-        for (int db = 0; db < kD / 32; ++db)
+        for (int i = 0; i < 4; ++i) {
+            const int row = 8 * i + srow;
+            st_ok[i] = !dense || q_first + row < p.n_dense_rows;
+            st_off[i] = q_row_off(row) + schunk * 16;
+        }
+        uint8_t* wr = stage + qcol * 128 + 8 * half;
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                uint2 v;
-                v.x = pack_bf16(oacc[db][4 * rq] * inv, oacc[db][4 * rq + 1] * inv);
-                v.y = pack_bf16(oacc[db][4 * rq + 2] * inv, oacc[db][4 * rq + 3] * inv);
-                *(uint2*)(dst + 32 * db + 8 * rq) = v;
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int dbp = 0; dbp < 2; ++dbp)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const f32x16& o = oacc[2 * pass + dbp];
+                    uint2 v;
+                    v.x = pack_bf16(o[4 * rq] * inv, o[4 * rq + 1] * inv);
+                    v.y = pack_bf16(o[4 * rq + 2] * inv, o[4 * rq + 3] * inv);
+                    *(uint2*)(wr + (((4 * dbp + rq) ^ (qcol & 7)) << 4)) = v;
+                }
+            __builtin_amdgcn_wave_barrier();   // (compiler: keep the reads below the writes above)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 8 * i + srow;
+                const uint4 x = *(const uint4*)(stage + row * 128 + ((schunk ^ (row & 7)) << 4));
+                if (st_ok[i]) *(uint4*)((uint8_t*)Oh + st_off[i] + pass * 128) = x;
             }
+            __builtin_amdgcn_wave_barrier();   // (... and the next pass's writes below these reads)
+        }
     }
 }
 
