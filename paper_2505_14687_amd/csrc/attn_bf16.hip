@@ -152,6 +152,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // q_first + i of its group, whose first token lies q_base bytes into the head
     uint32_t q_base = 0;
     int q_first;
+    bf16x8 qf[kD / 16];   // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
     if (dense) {
         n_tiles = (p.n_tokens + kBN - 1) / kBN;
         if (p.n_tokens % kBN) { mask_tile = n_tiles - 1; mask_valid = p.n_tokens % kBN; }
@@ -162,6 +163,20 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];
         const uint32_t grid_base = MODE == kJoint ? (uint32_t)p.grid_row0 * row_pitch : 0u;
+        // The queries are asked for first of all, with their row offset worked out in arithmetic
+        // rather than read from the table below: they come from HBM (nobody has touched them
+        // before) and everything up to the first barrier then happens in the shadow of that fetch.
+        {
+            const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
+                                 (gamma % geo.G[2]) * geo.g[2];
+            q_base = (uint32_t)((MODE == kJoint ? p.grid_row0 : 0) + q_origin) * row_pitch;
+            q_first = qt * BM + wave * 32;
+            const int t = q_first + qcol;
+            const uint32_t off = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
+            const uint8_t* src = (const uint8_t*)Qh + q_base + off + 16 * half;
+#pragma unroll
+            for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
+        }
         for (int t = tid; t < n_g; t += NT)
             s_rowbytes[t] = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
         const int cnt = p.kv_count[gamma];
@@ -179,10 +194,6 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         }
         n_tiles = n_lead + cnt * tiles_per_group;
         n_listed = cnt;
-        const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
-                             (gamma % geo.G[2]) * geo.g[2];
-        q_base = (uint32_t)((MODE == kJoint ? p.grid_row0 : 0) + q_origin) * row_pitch;
-        q_first = qt * BM + wave * 32;
     }
     if (n_tiles == 0) return;   // an empty list is outside the contract; never touch memory for it
     // byte offset inside the head of row i of this wave's 32 query (= output) rows; the rows of a
@@ -192,9 +203,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         return q_base + s_rowbytes[q_first + i];
     };
 
-    // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
-    bf16x8 qf[kD / 16];
-    {
+    if (dense) {
         const uint8_t* src = (const uint8_t*)Qh + q_row_off(qcol) + 16 * half;
 #pragma unroll
         for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
