@@ -109,7 +109,10 @@ grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int3
  * Supported (GRAT_ERR_UNSUPPORTED otherwise):
  *   GRAT_BF16: head_dim 128, tokens per group a multiple of 64;
  *   GRAT_F32 : head_dim 64 or 128, any group size;
- *   both     : (N - 1) * stride_n + head_dim < 2^31 elements, max_kv <= 8192.
+ *   both     : N < 2^31 tokens, stride_n < 2^24 elements, max_kv <= 8192; GRAT_BF16 also: the
+ *              rows of one group span less than 4 GiB (first to last token of a group, in bytes).
+ *              The tensors themselves may exceed 4 GiB: a packed [B][N][3][H][d] buffer of a long
+ *              sequence is passed as three pointers into it with stride_n = 3 * H * d.
  * bf16 path: scores, running max / sum and the output accumulator are fp32; softmax weights
  * are rounded to bf16 (nearest-even) before multiplying V; O is rounded to bf16 once.
  * Asynchronous on hip_stream.
@@ -136,6 +139,19 @@ grat_status grat_attention_global_fwd(const void* Q, const void* K, const void* 
                                       grat_dtype dtype, int32_t batch, int32_t heads,
                                       int32_t head_dim, int64_t stride_b, int64_t stride_h,
                                       int64_t stride_n, float scale, int32_t n_global,
+                                      int32_t global_first, int32_t ndim, const int32_t* grid,
+                                      const int32_t* group, const int32_t* d_kv_count,
+                                      const int32_t* d_kv_index, int32_t max_kv, void* hip_stream);
+
+/*
+ * The same again for Q, K and V that were never split: QKV is the output of a fused projection,
+ * one buffer [batch][n_global + N][3][heads][head_dim] (Q, K, V of a token side by side), and O is
+ * [batch][n_global + N][heads][head_dim], both contiguous.  Nothing is copied: the kernels read the
+ * three tensors through the token stride 3 * heads * head_dim.  n_global = 0 for a plain grid
+ * sequence.  Everything else, limits included, as in grat_attention_global_fwd.
+ */
+grat_status grat_attention_packed_fwd(const void* QKV, void* O, grat_dtype dtype, int32_t batch,
+                                      int32_t heads, int32_t head_dim, float scale, int32_t n_global,
                                       int32_t global_first, int32_t ndim, const int32_t* grid,
                                       const int32_t* group, const int32_t* d_kv_count,
                                       const int32_t* d_kv_index, int32_t max_kv, void* hip_stream);

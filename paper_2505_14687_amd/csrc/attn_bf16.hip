@@ -134,11 +134,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     const uint16_t* Qh = (const uint16_t*)p.Q + head_off;
     const uint16_t* Kh = (const uint16_t*)p.K + head_off;
     const uint16_t* Vh = (const uint16_t*)p.V + head_off;
-    uint16_t* Oh = (uint16_t*)p.O + head_off;
+    uint16_t* Oh = (uint16_t*)p.O + (int64_t)(bh / p.heads) * p.o_stride_b + (int64_t)(bh % p.heads) * p.o_stride_h;
     const int stride_n = p.stride_n;
 
-    // byte offsets (row * stride_n * 2): s_rowbytes[t] of intra-group token t relative to its group's
-    // first token, s_origin[i] of the first token of the i-th listed KV group
+    // s_rowbytes[t]: byte offset (row * stride_n * 2) of intra-group token t relative to its group's
+    // first token - a group spans less than 4 GiB; s_origin[i]: ROW of the first token of the i-th
+    // listed KV group - wave-uniform, turned into a 64-bit address in scalar registers, so the
+    // sequence itself may be as large as memory (packed [B][N][3][H][d] layouts of long sequences)
     uint32_t* s_rowbytes = (uint32_t*)s_dyn;
     uint32_t* s_origin = (uint32_t*)s_dyn + (MODE == kDense ? 0 : geo.group_tokens);
     const uint32_t row_pitch = (uint32_t)stride_n * 2u;   // bytes between consecutive tokens
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     int n_lead = 0;     // grouped tile of a joint sequence: leading KV tiles that hold the prompt tokens
     int mask_tile = -1, mask_valid = kBN;   // the one KV tile with fewer than 64 valid keys, if any
     // query rows of this wave: row i of its 32 is row q_first + i of the dense rows, resp. token
-    // q_first + i of its group, whose first token lies q_base bytes into the head
+    // q_first + i of its group, whose first token is row q_base of the head
     uint32_t q_base = 0;
     int q_first;
     bf16x8 qf[kD / 16];   // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
@@ -162,18 +164,18 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         const int qt = t_in_head % p.q_tiles;
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];
-        const uint32_t grid_base = MODE == kJoint ? (uint32_t)p.grid_row0 * row_pitch : 0u;
+        const uint32_t grid_base = MODE == kJoint ? (uint32_t)p.grid_row0 : 0u;   // first grid row
         // The queries are asked for first of all, with their row offset worked out in arithmetic
         // rather than read from the table below: they come from HBM (nobody has touched them
         // before) and everything up to the first barrier then happens in the shadow of that fetch.
         {
             const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                                  (gamma % geo.G[2]) * geo.g[2];
-            q_base = (uint32_t)((MODE == kJoint ? p.grid_row0 : 0) + q_origin) * row_pitch;
+            q_base = grid_base + (uint32_t)q_origin;
             q_first = qt * BM + wave * 32;
             const int t = q_first + qcol;
             const uint32_t off = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
-            const uint8_t* src = (const uint8_t*)Qh + q_base + off + 16 * half;
+            const uint8_t* src = (const uint8_t*)Qh + (uint64_t)q_base * row_pitch + off + 16 * half;
 #pragma unroll
             for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
         }
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             const int gid = p.kv_index[(int64_t)gamma * p.max_kv + i];
             s_origin[i] = grid_base +
                           (uint32_t)((gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
-                                     (gid % geo.G[2]) * geo.g[2]) * row_pitch;
+                                     (gid % geo.G[2]) * geo.g[2]);
         }
         __syncthreads();
         tiles_per_group = n_g / kBN;
@@ -198,9 +200,9 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     if (n_tiles == 0) return;   // an empty list is outside the contract; never touch memory for it
     // byte offset inside the head of row i of this wave's 32 query (= output) rows; the rows of a
     // dense tile past the last query re-read the last one and are never stored
-    auto q_row_off = [&](int i) -> uint32_t {
-        if (dense) return (uint32_t)(p.dense_row0 + min(q_first + i, p.n_dense_rows - 1)) * row_pitch;
-        return q_base + s_rowbytes[q_first + i];
+    auto q_row_off = [&](int i) -> uint64_t {
+        if (dense) return (uint64_t)(uint32_t)(p.dense_row0 + min(q_first + i, p.n_dense_rows - 1)) * row_pitch;
+        return (uint64_t)q_base * row_pitch + s_rowbytes[q_first + i];
     };
 
     if (dense) {
@@ -252,7 +254,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         if (MODE != kGrouped && (dense || t < n_lead)) {
             // consecutive rows: the whole sequence (dense tile) or the prompt tokens (leading tiles)
             const int first = dense ? 0 : p.global_row0, count = dense ? p.n_tokens : p.n_global;
-            a.base = (uint32_t)(first + t * kBN) * row_pitch;
+            a.base = (uint32_t)(first + t * kBN);
 #pragma unroll
             for (int k = 0; k < LPW; ++k)   // rows past the end re-read the last token (masked later)
                 a.off[k] = (uint32_t)min(load_row[k], count - 1 - t * kBN) * row_pitch + col[k];
@@ -269,7 +271,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
     auto issue_tile = [&](const uint16_t* head, uint8_t* dst_tile, const TileAddr& a) {
         // (made uniform again here: carried across iterations the offset may sit in a vector register)
-        const uint8_t* base = (const uint8_t*)head + __builtin_amdgcn_readfirstlane(a.base);
+        const uint8_t* base = (const uint8_t*)head + (uint64_t)__builtin_amdgcn_readfirstlane(a.base) * row_pitch;
 #pragma unroll
         for (int k = 0; k < LPW; ++k) {
             // LDS destination of this wave's piece; the hardware adds lane * 16
@@ -470,13 +472,19 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     {
         uint8_t* stage = &sK[0][0] + wave * 4096;   // [32 rows][8 chunks of 16 B], chunk ^= row & 7
         const int srow = lane >> 3, schunk = lane & 7;
-        uint32_t st_off[4];
+        uint64_t st_off[4];
         bool st_ok[4];
+        const uint32_t o_pitch = (uint32_t)p.o_stride_n * 2u;   // O may have a token stride of its own
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = 8 * i + srow;
             st_ok[i] = !dense || q_first + row < p.n_dense_rows;
-            st_off[i] = q_row_off(row) + schunk * 16;
+            uint64_t off = q_row_off(row);
+            if (o_pitch != row_pitch) {   // back to the row index (table entries are whole rows)
+                const uint32_t r = dense ? (uint32_t)(off / row_pitch) : q_base + s_rowbytes[q_first + row] / row_pitch;
+                off = (uint64_t)r * o_pitch;
+            }
+            st_off[i] = off + schunk * 16;
         }
         uint8_t* wr = stage + qcol * 128 + 8 * half;
 #pragma unroll

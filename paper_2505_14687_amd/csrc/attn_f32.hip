@@ -27,7 +27,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
     const float* Qh = (const float*)p.Q + head_off;
     const float* Kh = (const float*)p.K + head_off;
     const float* Vh = (const float*)p.V + head_off;
-    float* Oh = (float*)p.O + head_off;
+    float* Oh = (float*)p.O + (int64_t)(bh / p.heads) * p.o_stride_b + (int64_t)(bh % p.heads) * p.o_stride_h;
 
     const int T12 = geo.T[1] * geo.T[2];
     const int g12 = geo.g[1] * geo.g[2];
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
 
     if (q_valid) {
         const float inv = 1.f / l;
-        float4* dst = (float4*)(Oh + (int64_t)q_row * p.stride_n);
+        float4* dst = (float4*)(Oh + (int64_t)q_row * p.o_stride_n);
 #pragma unroll
         for (int c = 0; c < D / 4; ++c)
             dst[c] = make_float4(o[4 * c] * inv, o[4 * c + 1] * inv, o[4 * c + 2] * inv, o[4 * c + 3] * inv);

@@ -74,6 +74,15 @@ int64_t longest_list(const Geometry& geo, int32_t ndim, grat_pattern pattern, co
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// O's strides when they are not Q's: same rules as in check_tensors.
+grat_status check_out_strides(grat_dtype dtype, int32_t head_dim, int64_t b, int64_t h, int64_t n) {
+    if (n < head_dim || b < 0 || h < 0) return GRAT_ERR_BAD_DIMS;
+    const int vec = dtype == GRAT_BF16 ? 8 : 4;
+    if (n % vec || b % vec || h % vec) return GRAT_ERR_UNSUPPORTED;
+    if (n >= ((int64_t)1 << 24) || b >= ((int64_t)1 << 46) || h >= ((int64_t)1 << 46)) return GRAT_ERR_UNSUPPORTED;
+    return GRAT_OK;
+}
+
 // Checks shared by the grouped and the dense attention entry points.
 grat_status check_tensors(const void* Q, const void* K, const void* V, void* O, grat_dtype dtype,
                           int32_t batch, int32_t heads, int32_t head_dim, int64_t n_tokens,
@@ -89,7 +98,10 @@ grat_status check_tensors(const void* Q, const void* K, const void* V, void* O, 
     const int vec = dtype == GRAT_BF16 ? 8 : 4;
     if (stride_n % vec || stride_b % vec || stride_h % vec) return GRAT_ERR_UNSUPPORTED;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return GRAT_ERR_UNSUPPORTED;
-    if ((n_tokens - 1) * stride_n + head_dim >= kMaxElems) return GRAT_ERR_UNSUPPORTED;
+    // the token stride is kept in 32 bits (a 64-row tile then spans less than 4 GiB); the tensor
+    // itself may be larger than that: row addresses are formed in 64 bits
+    if (stride_n >= ((int64_t)1 << 24)) return GRAT_ERR_UNSUPPORTED;
+    if (stride_b >= ((int64_t)1 << 46) || stride_h >= ((int64_t)1 << 46)) return GRAT_ERR_UNSUPPORTED;
     if ((int64_t)batch * heads >= ((int64_t)1 << 24)) return GRAT_ERR_UNSUPPORTED;
     return GRAT_OK;
 }
@@ -135,9 +147,12 @@ extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid,
 }
 
 // Shared by grat_attention_fwd (n_global = 0) and grat_attention_global_fwd.
+struct OutStrides { int64_t b, h, n; };   // O's own strides (elements)
+
 static grat_status attention_fwd(const void* Q, const void* K, const void* V, void* O,
                                  grat_dtype dtype, int32_t batch, int32_t heads, int32_t head_dim,
-                                 int64_t stride_b, int64_t stride_h, int64_t stride_n, float scale,
+                                 int64_t stride_b, int64_t stride_h, int64_t stride_n,
+                                 OutStrides os, float scale,
                                  int32_t n_global, int32_t global_first, int32_t ndim,
                                  const int32_t* grid, const int32_t* group,
                                  const int32_t* d_kv_count, const int32_t* d_kv_index,
@@ -152,6 +167,8 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     st = check_tensors(Q, K, V, O, dtype, batch, heads, head_dim, seq_len, stride_b, stride_h,
                        stride_n, scale);
     if (st != GRAT_OK) return st;
+    st = check_out_strides(dtype, head_dim, os.b, os.h, os.n);
+    if (st != GRAT_OK) return st;
     for (int k = 0; k < 3; ++k)
         if (geo.T[k] % geo.g[k]) return GRAT_ERR_INDIVISIBLE;
     if (max_kv < 1) return GRAT_ERR_BUFFER_TOO_SMALL;
@@ -161,6 +178,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     AttnParams p{};
     p.Q = Q; p.K = K; p.V = V; p.O = O;
     p.stride_b = stride_b; p.stride_h = stride_h; p.stride_n = (int32_t)stride_n;
+    p.o_stride_b = os.b; p.o_stride_h = os.h; p.o_stride_n = (int32_t)os.n;
     p.batch = batch; p.heads = heads;
     p.scale_log2 = scale * 1.4426950408889634f;
     p.geo = geo;
@@ -171,6 +189,9 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     int bm;   // query rows per workgroup
     if (dtype == GRAT_BF16) {
         if (n_g % 64) return GRAT_ERR_UNSUPPORTED;
+        // byte offsets inside one group are kept in 32 bits
+        const int64_t span_rows = (int64_t)(geo.g[0] - 1) * geo.T[1] * geo.T[2] + (int64_t)(geo.g[1] - 1) * geo.T[2] + geo.g[2];
+        if (span_rows * stride_n * 2 >= ((int64_t)1 << 32)) return GRAT_ERR_UNSUPPORTED;
         if (n_g > 4096) return GRAT_ERR_UNSUPPORTED;   // intra-group offset table lives in LDS
         bm = n_g % 256 == 0 ? 256 : (n_g % 128 == 0 ? 128 : 64);
     } else {
@@ -207,7 +228,8 @@ extern "C" grat_status grat_attention_fwd(const void* Q, const void* K, const vo
                                           const int32_t* d_kv_count, const int32_t* d_kv_index,
                                           int32_t max_kv, void* hip_stream) {
     return attention_fwd(Q, K, V, O, dtype, batch, heads, head_dim, stride_b, stride_h, stride_n,
-                         scale, 0, 1, ndim, grid, group, d_kv_count, d_kv_index, max_kv, hip_stream);
+                         OutStrides{stride_b, stride_h, stride_n}, scale, 0, 1, ndim, grid, group,
+                         d_kv_count, d_kv_index, max_kv, hip_stream);
 }
 
 extern "C" grat_status grat_attention_global_fwd(const void* Q, const void* K, const void* V, void* O,
@@ -219,8 +241,31 @@ extern "C" grat_status grat_attention_global_fwd(const void* Q, const void* K, c
                                                  const int32_t* d_kv_count, const int32_t* d_kv_index,
                                                  int32_t max_kv, void* hip_stream) {
     return attention_fwd(Q, K, V, O, dtype, batch, heads, head_dim, stride_b, stride_h, stride_n,
-                         scale, n_global, global_first, ndim, grid, group, d_kv_count, d_kv_index,
-                         max_kv, hip_stream);
+                         OutStrides{stride_b, stride_h, stride_n}, scale, n_global, global_first,
+                         ndim, grid, group, d_kv_count, d_kv_index, max_kv, hip_stream);
+}
+
+extern "C" grat_status grat_attention_packed_fwd(const void* QKV, void* O, grat_dtype dtype,
+                                                 int32_t batch, int32_t heads, int32_t head_dim,
+                                                 float scale, int32_t n_global, int32_t global_first,
+                                                 int32_t ndim, const int32_t* grid, const int32_t* group,
+                                                 const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                                 int32_t max_kv, void* hip_stream) {
+    if (!QKV || !O) return GRAT_ERR_NULL;
+    if (batch < 1 || heads < 1 || head_dim < 1) return GRAT_ERR_BAD_DIMS;
+    if (dtype != GRAT_BF16 && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
+    Geometry geo;
+    const grat_status st = make_geometry(ndim, grid, group, &geo);
+    if (st != GRAT_OK) return st;
+    if (n_global < 0) return GRAT_ERR_BAD_DIMS;
+    const int64_t seq_len = geo.n_tokens + n_global;
+    const int64_t hd = (int64_t)heads * head_dim;            // one of Q, K, V of one token
+    const size_t esize = dtype == GRAT_BF16 ? 2 : 4;
+    const char* base = (const char*)QKV;
+    return attention_fwd(base, base + hd * esize, base + 2 * hd * esize, O, dtype, batch, heads,
+                         head_dim, seq_len * 3 * hd, head_dim, 3 * hd,
+                         OutStrides{seq_len * hd, head_dim, hd}, scale, n_global, global_first, ndim,
+                         grid, group, d_kv_count, d_kv_index, max_kv, hip_stream);
 }
 
 extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, const void* V, void* O,
@@ -236,6 +281,7 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     AttnParams p{};
     p.Q = Q; p.K = K; p.V = V; p.O = O;
     p.stride_b = stride_b; p.stride_h = stride_h; p.stride_n = (int32_t)stride_n;
+    p.o_stride_b = stride_b; p.o_stride_h = stride_h; p.o_stride_n = (int32_t)stride_n;
     p.batch = batch; p.heads = heads;
     p.scale_log2 = scale * 1.4426950408889634f;
     p.n_tokens = (int32_t)n_tokens;

@@ -22,8 +22,10 @@ struct AttnParams {
     const void* K;
     const void* V;
     void* O;
-    int64_t stride_b, stride_h;
-    int32_t stride_n;
+    int64_t stride_b, stride_h;      // Q, K, V: elements between batches / heads
+    int32_t stride_n;                // ... between tokens
+    int64_t o_stride_b, o_stride_h;  // the same for O
+    int32_t o_stride_n;
     int32_t batch, heads;
     float scale_log2;          // scale * log2(e)
     Geometry geo;

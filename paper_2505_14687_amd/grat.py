@@ -18,7 +18,8 @@ GRAT_OK = 0
 PATTERNS = {"block": 0, "cross": 1, "cross_planes": 2, "dense": 3}
 DTYPES = {torch.bfloat16: 0, torch.float32: 1}
 EXPORTS = ("grat_block_list_shape", "grat_build_block_lists", "grat_attention_fwd",
-           "grat_attention_global_fwd", "grat_dense_attention_fwd", "grat_status_string")
+           "grat_attention_global_fwd", "grat_attention_packed_fwd", "grat_dense_attention_fwd",
+           "grat_status_string")
 
 _i32, _i64, _f32, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
 _pi32 = ctypes.POINTER(ctypes.c_int32)
@@ -51,6 +52,9 @@ def lib() -> ctypes.CDLL:
                                                 _i64, _f32, _i32, _i32, _i32, _pi32, _pi32, _vp, _vp,
                                                 _i32, _vp]
         L.grat_attention_global_fwd.restype = _i32
+        L.grat_attention_packed_fwd.argtypes = [_vp, _vp, _i32, _i32, _i32, _i32, _f32, _i32, _i32, _i32,
+                                                _pi32, _pi32, _vp, _vp, _i32, _vp]
+        L.grat_attention_packed_fwd.restype = _i32
         L.grat_dense_attention_fwd.argtypes = [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i64, _i32,
                                                _i64, _i64, _i64, _f32, _vp]
         L.grat_dense_attention_fwd.restype = _i32
@@ -147,6 +151,28 @@ def grat_attention_global_fwd(Q, K, V, scale: float, n_global: int, global_first
                                          _stream_ptr(stream))
     if st != GRAT_OK:
         raise GratError(st, "grat_attention_global_fwd")
+    return O
+
+
+def grat_attention_packed_fwd(QKV, scale: float, grid: Sequence[int], group: Sequence[int], kv_count,
+                              kv_index, n_global: int = 0, global_first: bool = True, out=None,
+                              stream=None):
+    """QKV: contiguous [B, L, 3, H, d] (L = n_global + grid tokens); returns O as [B, L, H, d]."""
+    if QKV.dim() != 5 or QKV.shape[2] != 3 or not QKV.is_contiguous():
+        raise ValueError("expected a contiguous [B, L, 3, H, d] tensor")
+    if QKV.dtype not in DTYPES or not QKV.is_cuda:
+        raise ValueError("libgrat works on bf16 / fp32 device memory only")
+    B, L, _, H, d = QKV.shape
+    O = torch.empty((B, L, H, d), dtype=QKV.dtype, device=QKV.device) if out is None else out
+    if O.shape != (B, L, H, d) or O.dtype != QKV.dtype or not O.is_contiguous() or O.device != QKV.device:
+        raise ValueError("out must be a contiguous [B, L, H, d] tensor of QKV's dtype and device")
+    st = lib().grat_attention_packed_fwd(QKV.data_ptr(), O.data_ptr(), DTYPES[QKV.dtype], B, H, d,
+                                         float(scale), int(n_global), int(bool(global_first)),
+                                         len(grid), _ivec(grid), _ivec(group), kv_count.data_ptr(),
+                                         kv_index.data_ptr(), int(kv_index.shape[1]),
+                                         _stream_ptr(stream))
+    if st != GRAT_OK:
+        raise GratError(st, "grat_attention_packed_fwd")
     return O
 
 

@@ -82,7 +82,9 @@ def test_attention_argument_errors_return_before_any_launch():
     assert call(Q=fake + 2) == 6
     assert call(max_kv=0) == 5
     assert call(max_kv=100000) == 6
-    assert call(grid=(1 << 15, 1 << 15), group=(16, 16)) == 6   # offsets beyond 2^31 elements
+    assert call(sn=1 << 24) == 6                 # token stride beyond 2^24 elements
+    assert call(sn=1 << 23) == 6                 # bf16: one group's rows span 4 GiB or more
+    assert call(grid=(1 << 16, 1 << 16), group=(16, 16)) == 2   # 2^32 tokens
     d = L.grat_dense_attention_fwd
     assert d(fake, fake, fake, None, 0, 1, 1, 100, 128, 0, 0, 128, 0.1, None) == 1
     assert d(fake, fake, fake, fake, 0, 1, 1, 0, 128, 0, 0, 128, 0.1, None) == 2
@@ -110,4 +112,21 @@ def test_joint_sequence_argument_errors():
     assert call(n_global=-1) == 2
     assert call(dtype=1) == 6                      # prompt tokens on the fp32 path
     assert call(grid=(64, 60)) == 3
-    assert call(grid=(1 << 15, 1 << 15)) in (2, 6)
+    assert call(sn=1 << 24) == 6
+
+
+def test_packed_entry_argument_errors():
+    L = grat.lib()
+    i32x2 = ctypes.c_int32 * 2
+    fake = 0x1000
+    def call(QKV=fake, O=fake, dtype=0, batch=1, heads=2, d=128, n_global=0, grid=(64, 64), group=(16, 16),
+             cnt=fake, max_kv=9):
+        return L.grat_attention_packed_fwd(QKV, O, dtype, batch, heads, d, 0.1, n_global, 1, 2, i32x2(*grid),
+                                           i32x2(*group), cnt, fake, max_kv, None)
+    assert call(QKV=None) == 1 and call(O=None) == 1 and call(cnt=None) == 1
+    assert call(heads=0) == 2 and call(n_global=-1) == 2
+    assert call(dtype=3) == 6 and call(d=64) == 6
+    assert call(dtype=1, n_global=8) == 6
+    assert call(grid=(64, 60)) == 3
+    assert call(QKV=fake + 4) == 6                 # not 16-byte aligned
+    assert call(max_kv=0) == 5
