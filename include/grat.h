@@ -39,7 +39,7 @@ typedef enum {
     GRAT_ERR_NULL = 1,             /* a required pointer is NULL                               */
     GRAT_ERR_BAD_DIMS = 2,         /* ndim not in 1..3, a non-positive extent, negative radius,
                                       non-positive scale, strides that make rows overlap        */
-    GRAT_ERR_INDIVISIBLE = 3,      /* attention only: a group dim does not divide its grid dim  */
+    GRAT_ERR_INDIVISIBLE = 3,      /* joint sequences only: a group dim does not divide its grid dim */
     GRAT_ERR_BAD_PATTERN = 4,
     GRAT_ERR_BUFFER_TOO_SMALL = 5, /* max_kv smaller than the longest list                      */
     GRAT_ERR_UNSUPPORTED = 6,      /* shape / dtype outside what the kernels cover (see below)  */
@@ -100,14 +100,17 @@ grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int3
  *                          above; O must not alias Q, K or V
  *   batch, heads, head_dim tensor extents; the sequence length is prod grid[k]
  *   scale                  > 0, multiplies Q K^T (the paper uses 1/sqrt(head_dim))
- *   ndim, grid, group      as above; every group[k] must divide grid[k]
- *                          (GRAT_ERR_INDIVISIBLE otherwise)
+ *   ndim, grid, group      as above.  group[k] need not divide grid[k]: Eq. 2-4 / 9-11 are floor
+ *                          divisions, so the groups at the far border are the part of their
+ *                          box that lies inside the grid (lists as grat_build_block_lists
+ *                          writes them for the same grid and group)
  *   d_kv_count, d_kv_index, max_kv   lists in the format grat_build_block_lists writes (the
  *                          caller may also supply its own).  Every used entry must lie in
  *                          [0, G) and every count in [1, max_kv]; the kernel does not check
  *                          them and an entry outside that range is undefined behaviour.
  * Supported (GRAT_ERR_UNSUPPORTED otherwise):
- *   GRAT_BF16: head_dim 128, tokens per group a multiple of 64;
+ *   GRAT_BF16: head_dim 128, tokens per (whole) group a multiple of 64; with clipped border
+ *              groups also group[k] <= 1024 on the last two axes;
  *   GRAT_F32 : head_dim 64 or 128, any group size;
  *   both     : N < 2^31 tokens, stride_n < 2^24 elements, max_kv <= 8192; GRAT_BF16 also: the
  *              rows of one group span less than 4 GiB (first to last token of a group, in bytes).
@@ -133,7 +136,8 @@ grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void
  *                 zero: the grid tokens come first
  * A grid query attends the KV groups of its list plus every prompt token; a prompt query attends
  * the whole sequence.  Everything else as in grat_attention_fwd (which is the n_global = 0 case).
- * Supported: GRAT_BF16 (GRAT_F32 only with n_global = 0).
+ * Supported: GRAT_BF16 (GRAT_F32 only with n_global = 0); with n_global > 0 every group[k] must
+ * divide grid[k] (GRAT_ERR_INDIVISIBLE otherwise).
  */
 grat_status grat_attention_global_fwd(const void* Q, const void* K, const void* V, void* O,
                                       grat_dtype dtype, int32_t batch, int32_t heads,

@@ -87,7 +87,20 @@ __device__ __forceinline__ float sum_across_halves(float x) {
 //   kJoint    joint sequence of prompt tokens and grid tokens: the first p.n_dense_tiles tiles are
 //             dense tiles over the prompt rows (they attend the whole sequence), the others are
 //             grouped tiles whose walk starts with the prompt tokens' KV tiles.
-enum : int { kGrouped = 0, kDense = 1, kJoint = 2 };
+//   kRagged   kGrouped for a grid the group dims do not divide (Eq. 2-4 are floor divisions): a
+//             group at the far border is the part of its box inside the grid.  Boxes are still
+//             walked whole; tokens of a box that fall outside the grid are fetched from a clamped
+//             (valid, meaningless) address and get weight 0, queries outside are not stored.
+enum : int { kGrouped = 0, kDense = 1, kJoint = 2, kRagged = 3 };
+
+// Box coordinates of an intra-group token, packed for the border tests of kRagged: 12 + 10 + 10 bits.
+__device__ __forceinline__ uint32_t pack_coord(int c0, int c1, int c2) {
+    return (uint32_t)c0 << 20 | (uint32_t)c1 << 10 | (uint32_t)c2;
+}
+// every coordinate of c at most the matching one of lim (lim = largest coordinates inside the grid)
+__device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
+    return (c >> 20) <= (lim >> 20) && ((c >> 10) & 1023u) <= ((lim >> 10) & 1023u) && (c & 1023u) <= (lim & 1023u);
+}
 
 template <int NWAVES, int MODE>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
@@ -97,7 +110,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 
     __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
-    extern __shared__ int32_t s_dyn[];   // [n_g] row offsets inside a group, then [max_kv] group origins
+    extern __shared__ int32_t s_dyn[];   // [n_g] row offsets inside a group, then [max_kv] group origins (kRagged: and the two tables below)
+    constexpr bool kLists = MODE == kGrouped || MODE == kRagged;   // every KV tile comes from a listed group
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -142,7 +156,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // listed KV group - wave-uniform, turned into a 64-bit address in scalar registers, so the
     // sequence itself may be as large as memory (packed [B][N][3][H][d] layouts of long sequences)
     uint32_t* s_rowbytes = (uint32_t*)s_dyn;
-    uint32_t* s_origin = (uint32_t*)s_dyn + (MODE == kDense ? 0 : geo.group_tokens);
+    // kRagged: s_coord[t] = box coordinates of intra-group token t (behind s_rowbytes, so that it
+    // stays 16-byte aligned), s_limit[i] = largest box coordinates of listed group i that are still
+    // inside the grid (both packed)
+    uint32_t* s_coord = s_rowbytes + geo.group_tokens;
+    uint32_t* s_origin = (uint32_t*)s_dyn + (MODE == kDense ? 0 : (MODE == kRagged ? 2 : 1) * geo.group_tokens);
+    uint32_t* s_limit = s_origin + p.max_kv;
+    uint32_t q_limit = 0;   // kRagged: the same limit for the query group
     const uint32_t row_pitch = (uint32_t)stride_n * 2u;   // bytes between consecutive tokens
 
     int n_tiles;        // KV tiles to walk
@@ -165,6 +185,11 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];
         const uint32_t grid_base = MODE == kJoint ? (uint32_t)p.grid_row0 : 0u;   // first grid row
+        auto box_limit = [&](int gid) {   // largest box coordinates of group gid inside the grid
+            const int p0 = gid / G12, p1 = (gid / geo.G[2]) % geo.G[1], p2 = gid % geo.G[2];
+            return pack_coord(min(geo.g[0], geo.T[0] - p0 * geo.g[0]) - 1, min(geo.g[1], geo.T[1] - p1 * geo.g[1]) - 1,
+                              min(geo.g[2], geo.T[2] - p2 * geo.g[2]) - 1);
+        };
         // The queries are asked for first of all, with their row offset worked out in arithmetic
         // rather than read from the table below: they come from HBM (nobody has touched them
         // before) and everything up to the first barrier then happens in the shadow of that fetch.
@@ -174,19 +199,28 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             q_base = grid_base + (uint32_t)q_origin;
             q_first = qt * BM + wave * 32;
             const int t = q_first + qcol;
-            const uint32_t off = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
+            const int c0 = t / g12, c1 = (t / geo.g[2]) % geo.g[1], c2 = t % geo.g[2];
+            uint32_t off = (uint32_t)(c0 * T12 + c1 * geo.T[2] + c2) * row_pitch;
+            if (MODE == kRagged) {
+                q_limit = box_limit(gamma);
+                if (!coord_inside(pack_coord(c0, c1, c2), q_limit)) off = 0;   // a query outside the grid: any valid row will do
+            }
             const uint8_t* src = (const uint8_t*)Qh + (uint64_t)q_base * row_pitch + off + 16 * half;
 #pragma unroll
             for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
         }
-        for (int t = tid; t < n_g; t += NT)
-            s_rowbytes[t] = (uint32_t)((t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2]) * row_pitch;
+        for (int t = tid; t < n_g; t += NT) {
+            const int c0 = t / g12, c1 = (t / geo.g[2]) % geo.g[1], c2 = t % geo.g[2];
+            s_rowbytes[t] = (uint32_t)(c0 * T12 + c1 * geo.T[2] + c2) * row_pitch;
+            if (MODE == kRagged) s_coord[t] = pack_coord(c0, c1, c2);
+        }
         const int cnt = p.kv_count[gamma];
         for (int i = tid; i < cnt; i += NT) {
             const int gid = p.kv_index[(int64_t)gamma * p.max_kv + i];
             s_origin[i] = grid_base +
                           (uint32_t)((gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
                                      (gid % geo.G[2]) * geo.g[2]);
+            if (MODE == kRagged) s_limit[i] = box_limit(gid);
         }
         __syncthreads();
         tiles_per_group = n_g / kBN;
@@ -251,7 +285,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // Offsets of a tile are looked up one tile before it is fetched, so the table reads never sit
     // between a barrier and the loads that follow it.
     auto tile_addr = [&](TileAddr& a, const uint32_t* col, int t, int& gi, int& j) {
-        if (MODE != kGrouped && (dense || t < n_lead)) {
+        if (!kLists && (dense || t < n_lead)) {
             // consecutive rows: the whole sequence (dense tile) or the prompt tokens (leading tiles)
             const int first = dense ? 0 : p.global_row0, count = dense ? p.n_tokens : p.n_global;
             a.base = (uint32_t)(first + t * kBN);
@@ -260,8 +294,14 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
                 a.off[k] = (uint32_t)min(load_row[k], count - 1 - t * kBN) * row_pitch + col[k];
         } else {
             a.base = __builtin_amdgcn_readfirstlane(s_origin[min(gi, n_listed - 1)]);   // (may be asked past the end)
+            // kRagged: rows of the box beyond the last token of the sequence are pulled back onto it
+            const uint64_t to_end = (uint64_t)((uint32_t)geo.n_tokens - 1u - a.base) * row_pitch;
+            const uint32_t max_off = to_end > 0xffffffffull ? 0xffffffffu : (uint32_t)to_end;
 #pragma unroll
-            for (int k = 0; k < LPW; ++k) a.off[k] = s_rowbytes[j * kBN + load_row[k]] + col[k];
+            for (int k = 0; k < LPW; ++k) {
+                const uint32_t o = s_rowbytes[j * kBN + load_row[k]];
+                a.off[k] = (MODE == kRagged ? min(o, max_off) : o) + col[k];
+            }
             if (++j == tiles_per_group) { j = 0; ++gi; }
         }
     };
@@ -359,6 +399,28 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
                 if (key >= mask_valid) S[kb][r] = -INFINITY;
             }
     };
+    // kRagged: called once per KV tile, in walk order.  Keys of a border group's box that lie outside
+    // the grid get weight 0.  (The first tile of every box holds its first token, which is always
+    // inside, so the first tile of a walk never ends up without a finite score.)
+    int gi_m = 0, j_m = 0;   // list entry / tile-in-group of the tile whose scores are in S
+    const uint32_t full_box = pack_coord(geo.g[0] - 1, geo.g[1] - 1, geo.g[2] - 1);
+    auto mask_outside = [&]() {
+        const uint32_t lim = __builtin_amdgcn_readfirstlane(s_limit[min(gi_m, n_listed - 1)]);
+        if (lim != full_box) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    // accumulator registers 4*rq .. 4*rq+3 hold 4 consecutive keys
+                    const uint4 c = *(const uint4*)&s_coord[j_m * kBN + 32 * kb + 8 * rq + 4 * half];
+                    if (!coord_inside(c.x, lim)) S[kb][4 * rq] = -INFINITY;
+                    if (!coord_inside(c.y, lim)) S[kb][4 * rq + 1] = -INFINITY;
+                    if (!coord_inside(c.z, lim)) S[kb][4 * rq + 2] = -INFINITY;
+                    if (!coord_inside(c.w, lim)) S[kb][4 * rq + 3] = -INFINITY;
+                }
+        }
+        if (++j_m == tiles_per_group) { j_m = 0; ++gi_m; }
+    };
     // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to be:
     // the common path computes exp2(c*s - c*m_ref) without looking at the tile's own maximum and
     // checks afterwards that no row sum of the tile left the safe range.  Only then (and on the
@@ -418,8 +480,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va);
         // (grouped: looked up unconditionally, so that the table reads stay inside the straight-line
         // block that follows instead of becoming a block of their own with its own waits)
-        if (MODE == kGrouped || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
-        if (MODE == kGrouped || t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
+        if (kLists || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
+        if (kLists || t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
 
     // tile 0: QK and weights only
@@ -427,7 +489,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         swap_barrier(0);
         qk_half(0, 0);
         qk_half(0, 1);
-        if (MODE != kGrouped && mask_tile == 0) mask_tail();
+        if (!kLists && mask_tile == 0) mask_tail();
+        if (MODE == kRagged) mask_outside();
         first_softmax(pwA);
     }
     // tile t >= 1: QK(t), weights(t) and PV(t-1) in one straight-line block; the statement order
@@ -437,7 +500,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         float ls = 0.f;
         qk_half(t & 1, 0);
         qk_half(t & 1, 1);
-        if (MODE != kGrouped && t == mask_tile) mask_tail();
+        if (!kLists && t == mask_tile) mask_tail();
+        if (MODE == kRagged) mask_outside();
         exp_half(0, pw_cur, ls);
         pv_half((t - 1) & 1, 0, pw_prev);
         exp_half(1, pw_cur, ls);
@@ -479,6 +543,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         for (int i = 0; i < 4; ++i) {
             const int row = 8 * i + srow;
             st_ok[i] = !dense || q_first + row < p.n_dense_rows;
+            if (MODE == kRagged) st_ok[i] = coord_inside(s_coord[q_first + row], q_limit);
             uint64_t off = q_row_off(row);
             if (o_pitch != row_pitch) {   // back to the row index (table entries are whole rows)
                 const uint32_t r = dense ? (uint32_t)(off / row_pitch) : q_base + s_rowbytes[q_first + row] / row_pitch;
@@ -514,8 +579,10 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 template <int NWAVES>
 static hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
     const dim3 block(NWAVES * 64);
-    const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * ((size_t)p.geo.group_tokens + p.max_kv);
-    if (mode == kDense) {
+    const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * (mode == kRagged ? 2 : 1) * ((size_t)p.geo.group_tokens + p.max_kv);
+    if (mode == kRagged) {
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kRagged>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+    } else if (mode == kDense) {
         hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else if (mode == kGrouped) {
         hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);

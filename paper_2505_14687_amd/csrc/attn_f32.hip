@@ -4,6 +4,8 @@
 // path (inputs, scores, softmax and accumulation all fp32); throughput is not its purpose.
 // One 64-lane wavefront owns up to 64 queries of one group; K/V rows of the attendable groups
 // are staged through LDS 32 tokens at a time and every lane reads them as broadcasts.
+// Group dims need not divide the grid (Eq. 2-4 are floor divisions): a group at the far border
+// is the part of its box that lies inside the grid, and its tokens are enumerated over that part.
 #include "grat_common.h"
 
 namespace grat {
@@ -30,17 +32,23 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
     float* Oh = (float*)p.O + (int64_t)(bh / p.heads) * p.o_stride_b + (int64_t)(bh % p.heads) * p.o_stride_h;
 
     const int T12 = geo.T[1] * geo.T[2];
-    const int g12 = geo.g[1] * geo.g[2];
     const int G12 = geo.G[1] * geo.G[2];
-    const int n_g = geo.group_tokens;
 
-    // token row of intra-group token t of the group whose first token row is `origin`
-    auto token_row = [&](int origin, int t) {
-        return origin + (t / g12) * T12 + ((t / geo.g[2]) % geo.g[1]) * geo.T[2] + t % geo.g[2];
+    // A group as its first token row and the extents of its box inside the grid.
+    struct Box { int origin, v1, v2, tokens; };
+    auto group_box = [&](int gid) {
+        const int p0 = gid / G12, p1 = (gid / geo.G[2]) % geo.G[1], p2 = gid % geo.G[2];
+        const int v0 = min(geo.g[0], geo.T[0] - p0 * geo.g[0]);
+        Box b;
+        b.v1 = min(geo.g[1], geo.T[1] - p1 * geo.g[1]);
+        b.v2 = min(geo.g[2], geo.T[2] - p2 * geo.g[2]);
+        b.origin = p0 * geo.g[0] * T12 + p1 * geo.g[1] * geo.T[2] + p2 * geo.g[2];
+        b.tokens = v0 * b.v1 * b.v2;
+        return b;
     };
-    auto group_origin = [&](int gid) {
-        return (gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
-               (gid % geo.G[2]) * geo.g[2];
+    // token row of the t-th token of a group (last axis fastest inside its box)
+    auto token_row = [&](const Box& b, int t) {
+        return b.origin + (t / (b.v1 * b.v2)) * T12 + ((t / b.v2) % b.v1) * geo.T[2] + t % b.v2;
     };
 
     int gamma = 0, q_row, n_lists, list_tokens;
@@ -52,11 +60,13 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
         list_tokens = p.n_tokens;
     } else {
         gamma = t_in_head / p.q_tiles;
+        const Box qb = group_box(gamma);
+        if ((t_in_head % p.q_tiles) * 64 >= qb.tokens) return;   // a border group with fewer query tiles
         const int t = (t_in_head % p.q_tiles) * 64 + lane;
-        q_valid = t < n_g;
-        q_row = token_row(group_origin(gamma), q_valid ? t : 0);
+        q_valid = t < qb.tokens;
+        q_row = token_row(qb, q_valid ? t : 0);
         n_lists = p.kv_count[gamma];
-        list_tokens = n_g;
+        list_tokens = 0;   // per listed group, below
     }
     if (!q_valid && DENSE) q_row = p.n_tokens - 1;
 
@@ -74,7 +84,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
     float m = -INFINITY, l = 0.f;
 
     for (int li = 0; li < n_lists; ++li) {
-        const int origin = DENSE ? 0 : group_origin(p.kv_index[(int64_t)gamma * p.max_kv + li]);
+        Box kb{0, 1, 1, 0};
+        if (!DENSE) {
+            kb = group_box(p.kv_index[(int64_t)gamma * p.max_kv + li]);
+            list_tokens = kb.tokens;
+        }
         for (int t0 = 0; t0 < list_tokens; t0 += kF32Keys) {
             const int n_valid = min(kF32Keys, list_tokens - t0);
             __syncthreads();
@@ -82,7 +96,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
             for (int c = lane; c < kF32Keys * (D / 4); c += 64) {
                 const int kk = c / (D / 4), col = c % (D / 4);
                 if (kk < n_valid) {
-                    const int row = DENSE ? t0 + kk : token_row(origin, t0 + kk);
+                    const int row = DENSE ? t0 + kk : token_row(kb, t0 + kk);
                     const int64_t off = (int64_t)row * p.stride_n + 4 * col;
                     *(float4*)&sK[kk][4 * col] = *(const float4*)(Kh + off);
                     *(float4*)&sV[kk][4 * col] = *(const float4*)(Vh + off);

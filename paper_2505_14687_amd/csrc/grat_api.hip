@@ -169,8 +169,9 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     if (st != GRAT_OK) return st;
     st = check_out_strides(dtype, head_dim, os.b, os.h, os.n);
     if (st != GRAT_OK) return st;
-    for (int k = 0; k < 3; ++k)
-        if (geo.T[k] % geo.g[k]) return GRAT_ERR_INDIVISIBLE;
+    bool ragged = false;   // a group dim does not divide its grid dim: groups at the far border are clipped
+    for (int k = 0; k < 3; ++k) ragged = ragged || geo.T[k] % geo.g[k] != 0;
+    if (ragged && n_global > 0) return GRAT_ERR_INDIVISIBLE;   // joint sequences: whole groups only
     if (max_kv < 1) return GRAT_ERR_BUFFER_TOO_SMALL;
     if (max_kv > kMaxListLen) return GRAT_ERR_UNSUPPORTED;
     if (n_global > 0 && dtype != GRAT_BF16) return GRAT_ERR_UNSUPPORTED;
@@ -203,7 +204,9 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
-    int mode = 0;
+    int mode = ragged ? 3 : 0;
+    // the clipped-box tests of the bf16 kernel pack box coordinates into 12 + 10 + 10 bits
+    if (ragged && dtype == GRAT_BF16 && (geo.g[1] > 1024 || geo.g[2] > 1024)) return GRAT_ERR_UNSUPPORTED;
     if (n_global > 0) {   // joint sequence: prompt rows become dense tiles launched ahead of the rest
         mode = 2;
         p.n_global = n_global;

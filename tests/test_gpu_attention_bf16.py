@@ -146,6 +146,36 @@ def test_small_grouped(grid, group, pattern, radius):
     assert_close(got, want, "bf16", f"{grid} {group} {pattern}")
 
 
+@pytest.mark.parametrize("grid,group,pattern,radius", [
+    ((40, 56), (16, 16), "block", (1, 1)),            # last groups 8 x 8 of 16 x 16: whole KV tiles outside
+    ((40, 56), (16, 16), "cross", (0, 0)),
+    ((33, 47), (8, 8), "block", (1, 1)),              # 2-wave workgroups; one row / seven columns left over
+    ((36, 40), (8, 16), "cross", (0, 0)),             # 4-wave workgroups
+    ((70, 90), (32, 32), "block", (1, 1)),            # 1024-token boxes: border query tiles wholly outside
+    ((5, 20, 28), (2, 8, 8), "block", (1, 1, 1)),     # ragged on all three axes
+    ((5, 20, 28), (2, 8, 8), "cross_planes", (0, 0, 0)),
+    ((1000,), (128,), "block", (1,)),                 # 1D, last group of 104 tokens
+    ((17, 16), (16, 16), "block", (1, 1)),            # the last group is a single grid row
+])
+def test_group_dims_not_dividing_the_grid(grid, group, pattern, radius):
+    """Eq. 2-4 are floor divisions: border groups are the part of their box inside the grid."""
+    got, want = small_case(2, 2, grid, group, pattern, radius, q_gain=2.0, seed=94)
+    assert_close(got, want, "bf16", f"ragged {grid} {group} {pattern}")
+
+
+def test_last_token_of_the_tensor_is_the_clamp_target():
+    """A ragged grid whose K/V end exactly at the end of their allocation: rows of border boxes past
+    the last token must be fetched from inside the tensor."""
+    grid, group = (24, 40), (16, 16)
+    host = synth.make_qkv(1, 1, 24 * 40, 128, "bf16", 95)
+    dev = [to_device(x).clone() for x in host]        # exact-size allocations
+    scale = 1.0 / math.sqrt(128)
+    count, index = grat.grat_build_block_lists(grid, group, "block", (1, 1))
+    O = grat.grat_attention_fwd(*dev, scale, grid, group, count, index)
+    torch.cuda.synchronize()
+    assert_close(to_f64(O), orc.grat_attention(*host, grid, group, "block", (1, 1), scale), "bf16", "ragged tail")
+
+
 @pytest.mark.parametrize("pattern,radius", [("block", (1, 1)), ("cross", (0, 0))])
 def test_peaked_softmax(pattern, radius):
     """Q scaled by 4: near one-hot weights, the running max keeps moving."""

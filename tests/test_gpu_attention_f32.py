@@ -49,6 +49,25 @@ def test_small_shapes(grid, group, pattern, radius, heads, d):
     assert_close(got, want, "f32", f"{grid} {group} {pattern}")
 
 
+@pytest.mark.parametrize("grid,group,pattern,radius,d", [
+    ((30, 44), (8, 8), "block", (1, 1), 64),              # last groups 6 rows / 4 columns deep
+    ((30, 44), (8, 8), "cross", (0, 0), 64),
+    ((5, 7), (2, 3), "block", (1, 1), 64),                # the oracle's own ragged pin shape
+    ((70,), (16,), "block", (1,), 128),                   # 1D, last group of 6 tokens
+    ((5, 18, 20), (2, 8, 8), "block", (1, 1, 1), 64),     # ragged on all three axes
+    ((5, 18, 20), (2, 8, 8), "cross_planes", (0, 0, 0), 64),
+    ((100, 9), (40, 4), "cross", (0, 0), 64),             # 160-token boxes: border groups with fewer query tiles
+])
+def test_group_dims_not_dividing_the_grid(grid, group, pattern, radius, d):
+    """Eq. 2-4 are floor divisions: border groups are the part of their box inside the grid."""
+    N = int(np.prod(grid))
+    Q, K, V = synth.make_qkv(2, 2, N, d, "f32", 79, q_gain=2.0)
+    scale = 1.0 / math.sqrt(d)
+    want = orc.grat_attention(Q, K, V, grid, group, pattern, radius, scale)
+    got = run_grouped(Q, K, V, grid, group, pattern, radius, scale)
+    assert_close(got, want, "f32", f"ragged {grid} {group} {pattern}")
+
+
 @pytest.mark.parametrize("N", [1, 31, 64, 1000])
 def test_dense(N):
     Q, K, V = synth.make_qkv(1, 3, N, 64, "f32", 78, q_gain=3.0)
