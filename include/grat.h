@@ -61,7 +61,8 @@ typedef enum {
     GRAT_DENSE = 3
 } grat_pattern;
 
-typedef enum { GRAT_BF16 = 0, GRAT_F32 = 1 } grat_dtype;
+/* element type of Q, K, V and O: bfloat16, IEEE binary32, IEEE binary16 */
+typedef enum { GRAT_BF16 = 0, GRAT_F32 = 1, GRAT_F16 = 2 } grat_dtype;
 
 /*
  * Sizes of the block lists for a pattern (host only, touches no GPU).
@@ -109,15 +110,15 @@ grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int3
  *                          [0, G) and every count in [1, max_kv]; the kernel does not check
  *                          them and an entry outside that range is undefined behaviour.
  * Supported (GRAT_ERR_UNSUPPORTED otherwise):
- *   GRAT_BF16: head_dim 128, tokens per (whole) group a multiple of 64; with clipped border
+ *   GRAT_BF16, GRAT_F16: head_dim 128, tokens per (whole) group a multiple of 64; with clipped border
  *              groups also group[k] <= 1024 on the last two axes;
  *   GRAT_F32 : head_dim 64 or 128, any group size;
- *   both     : N < 2^31 tokens, stride_n < 2^24 elements, max_kv <= 8192; GRAT_BF16 also: the
+ *   all      : N < 2^31 tokens, stride_n < 2^24 elements, max_kv <= 8192; 16-bit types also: the
  *              rows of one group span less than 4 GiB (first to last token of a group, in bytes).
  *              The tensors themselves may exceed 4 GiB: a packed [B][N][3][H][d] buffer of a long
  *              sequence is passed as three pointers into it with stride_n = 3 * H * d.
- * bf16 path: scores, running max / sum and the output accumulator are fp32; softmax weights
- * are rounded to bf16 (nearest-even) before multiplying V; O is rounded to bf16 once.
+ * 16-bit paths: scores, running max / sum and the output accumulator are fp32; softmax weights
+ * are rounded to the element type (nearest-even) before multiplying V; O is rounded once.
  * Asynchronous on hip_stream.
  */
 grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void* O,
@@ -136,7 +137,7 @@ grat_status grat_attention_fwd(const void* Q, const void* K, const void* V, void
  *                 zero: the grid tokens come first
  * A grid query attends the KV groups of its list plus every prompt token; a prompt query attends
  * the whole sequence.  Everything else as in grat_attention_fwd (which is the n_global = 0 case).
- * Supported: GRAT_BF16 (GRAT_F32 only with n_global = 0); with n_global > 0 every group[k] must
+ * Supported: GRAT_BF16 and GRAT_F16 (GRAT_F32 only with n_global = 0); with n_global > 0 every group[k] must
  * divide grid[k] (GRAT_ERR_INDIVISIBLE otherwise).
  */
 grat_status grat_attention_global_fwd(const void* Q, const void* K, const void* V, void* O,

@@ -152,7 +152,7 @@ def decode_bf16(bits: np.ndarray) -> np.ndarray:
 
 
 def as_f64(x: np.ndarray) -> np.ndarray:
-    """Inputs arrive as float32/float64 values or as uint16 bf16 bit patterns."""
+    """Inputs arrive as float16/float32/float64 values or as uint16 bf16 bit patterns."""
     return decode_bf16(x) if x.dtype == np.uint16 else np.asarray(x, dtype=np.float64)
 
 

@@ -35,6 +35,9 @@ namespace grat {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(8))) short frag8;   // 8 sixteen-bit elements of either type
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -45,7 +48,6 @@ constexpr int kD = 128;               // head_dim
 constexpr int kBN = 64;               // KV tokens per LDS tile
 constexpr int kRowBytes = kD * 2;     // 256 B per token row
 constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB
-constexpr float kSumLimit = 0x1p+40f;   // a lane's tile row sum (32 weights) beyond this forces a new reference maximum
 
 // LDS tiles are unpadded [64 rows][16 chunks of 16 B]; the chunk index is XOR-swizzled per row so
 // that the fragment reads are bank-conflict free.  K is read with ds_read_b128 by lanes holding
@@ -55,10 +57,36 @@ constexpr float kSumLimit = 0x1p+40f;   // a lane's tile row sum (32 weights) be
 __device__ __forceinline__ int k_swizzle(int row) { return ((row & 7) << 1) | ((row >> 3) & 1); }
 __device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 2; }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
+// What depends on the 16-bit element type (F16 = false: bfloat16, true: IEEE half).  Fragments
+// travel as type-neutral frag8 and are reinterpreted at the MFMA.
+template <bool F16>
+struct Elem {
+    // a lane's tile row sum (32 weights) beyond this forces a new reference maximum: every single
+    // weight then stays inside the type's range (half: 65504) with its full relative precision
+    static constexpr float kSumLimit = F16 ? 0x1p+15f : 0x1p+40f;
+    static __device__ __forceinline__ f32x16 mfma(frag8 a, frag8 b, f32x16 c) {
+        if constexpr (F16)
+            return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+        else
+            return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    // two fp32 values rounded to nearest-even and packed (lo in the low half)
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
+        const f32x2 v = {lo, hi};
+        if constexpr (F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+        else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
+    // acc + both halves of a packed pair (one packed dot product with (1, 1))
+    static __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
+        if constexpr (F16) {
+            const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+            return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), ones, acc, false);
+        } else {
+            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+            return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, acc, false);
+        }
+    }
+};
 
 // Exchange between the two lanes that hold the same query (lane and lane ^ 32) with one
 // v_permlane32_swap.  The two results are copied to scalars before they are reinterpreted:
@@ -102,8 +130,9 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
     return (c >> 20) <= (lim >> 20) && ((c >> 10) & 1023u) <= ((lim >> 10) & 1023u) && (c & 1023u) <= (lim & 1023u);
 }
 
-template <int NWAVES, int MODE>
+template <int NWAVES, int MODE, bool F16>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
+    using E = Elem<F16>;
     constexpr int NT = NWAVES * 64;
     constexpr int BM = NWAVES * 32;
     constexpr int LPW = 16 / NWAVES;   // 1-KiB direct loads per wave per 16-KiB tile
@@ -174,7 +203,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // q_first + i of its group, whose first token is row q_base of the head
     uint32_t q_base = 0;
     int q_first;
-    bf16x8 qf[kD / 16];   // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
+    frag8 qf[kD / 16];   // Q^T fragments (B operand): this lane's query, dims 16*ks + 8*half .. +7
     if (dense) {
         n_tiles = (p.n_tokens + kBN - 1) / kBN;
         if (p.n_tokens % kBN) { mask_tile = n_tiles - 1; mask_valid = p.n_tokens % kBN; }
@@ -207,7 +236,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             }
             const uint8_t* src = (const uint8_t*)Qh + (uint64_t)q_base * row_pitch + off + 16 * half;
 #pragma unroll
-            for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
+            for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const frag8*)(src + 32 * ks);
         }
         for (int t = tid; t < n_g; t += NT) {
             const int c0 = t / g12, c1 = (t / geo.g[2]) % geo.g[1], c2 = t % geo.g[2];
@@ -242,7 +271,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     if (dense) {
         const uint8_t* src = (const uint8_t*)Qh + q_row_off(qcol) + 16 * half;
 #pragma unroll
-        for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const bf16x8*)(src + 32 * ks);
+        for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const frag8*)(src + 32 * ks);
     }
 
     f32x16 oacc[kD / 32];                 // O^T accumulator: 4 blocks of 32 head dims
@@ -338,9 +367,9 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         const uint8_t* kt = sK[kbuf] + k_lane_base + kb * 32 * kRowBytes;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            bf16x8 f[4];
+            frag8 f[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) f[i] = *(const bf16x8*)(kt + (((2 * (4 * j + i)) ^ k_x) << 4));
+            for (int i = 0; i < 4; ++i) f[i] = *(const frag8*)(kt + (((2 * (4 * j + i)) ^ k_x) << 4));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int ks = 4 * j + i;
@@ -348,9 +377,9 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
                     f32x16 zero;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-                    S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], zero, 0, 0, 0);
+                    S[kb] = E::mfma(f[i], qf[ks], zero);
                 } else {
-                    S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[ks], S[kb], 0, 0, 0);
+                    S[kb] = E::mfma(f[i], qf[ks], S[kb]);
                 }
             }
         }
@@ -360,34 +389,33 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         const uint8_t* vt = sV[vbuf] + v_lane_base;
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-            bf16x8 f[4];
+            frag8 f[4];
 #pragma unroll
             for (int db = 0; db < kD / 32; ++db) {
                 const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
                 const uint8_t* src = vt + (32 * kb + 16 * s2) * kRowBytes + col;
                 const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))src);
                 const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(src + 8 * kRowBytes));
-                f[db] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                f[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
             const uint32_t* w = &pw[kb][4 * s2];
-            const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            const frag8 b = __builtin_bit_cast(frag8, make_uint4(w[0], w[1], w[2], w[3]));
 #pragma unroll
             for (int db = 0; db < kD / 32; ++db)
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], b, oacc[db], 0, 0, 0);
+                oacc[db] = E::mfma(f[db], b, oacc[db]);
         }
     };
     // Weights of key block kb against the current reference maximum; adds this lane's share of the
     // row sum (taken over the rounded weights) to ls.  The packed dot product does the summing.
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     auto exp_half = [&](int kb, uint32_t (&pw)[2][8], float& ls) {
         const float mc = m_ref * c;
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], c, -mc));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], c, -mc));
-            const uint32_t w = pack_bf16(p0, p1);
+            const uint32_t w = E::pack(p0, p1);
             pw[kb][r >> 1] = w;
-            ls = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, ls, false);
+            ls = E::add_pair(w, ls);
         }
     };
     auto mask_tail = [&]() {   // the ragged tile: keys past the end of their run get weight 0
@@ -429,7 +457,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // quotient O / l; this one keeps every weight below 2^40, which bf16 and the fp32 accumulators
     // hold without loss of relative accuracy.
     auto finish_softmax = [&](uint32_t (&pw)[2][8], float ls) {
-        if (__builtin_amdgcn_ballot_w64(!(ls < kSumLimit)) != 0) {
+        if (__builtin_amdgcn_ballot_w64(!(ls < E::kSumLimit)) != 0) {
             float mx = S[0][0];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -560,8 +588,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
                 for (int rq = 0; rq < 4; ++rq) {
                     const f32x16& o = oacc[2 * pass + dbp];
                     uint2 v;
-                    v.x = pack_bf16(o[4 * rq] * inv, o[4 * rq + 1] * inv);
-                    v.y = pack_bf16(o[4 * rq + 2] * inv, o[4 * rq + 3] * inv);
+                    v.x = E::pack(o[4 * rq] * inv, o[4 * rq + 1] * inv);
+                    v.y = E::pack(o[4 * rq + 2] * inv, o[4 * rq + 3] * inv);
                     *(uint2*)(wr + (((4 * dbp + rq) ^ (qcol & 7)) << 4)) = v;
                 }
             __builtin_amdgcn_wave_barrier();   // (compiler: keep the reads below the writes above)
@@ -576,30 +604,35 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     }
 }
 
-template <int NWAVES>
+template <int NWAVES, bool F16>
 static hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
     const dim3 block(NWAVES * 64);
     const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * (mode == kRagged ? 2 : 1) * ((size_t)p.geo.group_tokens + p.max_kv);
     if (mode == kRagged) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kRagged>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kRagged, F16>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else if (mode == kDense) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense, F16>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else if (mode == kGrouped) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped, F16>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else {
         const int blocks = xcd_padded_blocks(p.n_dense_tiles) + xcd_padded_blocks(p.total_tiles);
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kJoint>), dim3(blocks), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kJoint, F16>), dim3(blocks), block, dyn, stream, p);
     }
     return hipGetLastError();
 }
 
 // The host computed p.q_tiles (and p.q_tiles_dense) for the query-tile height chosen here:
-// 256, 128 or 64 rows.
-hipError_t launch_attn_bf16(const AttnParams& p, int mode, hipStream_t stream) {
+// 256, 128 or 64 rows.  f16: the elements are IEEE half instead of bfloat16.
+hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, hipStream_t stream) {
     const int bm = mode == kDense ? 256 : (p.geo.group_tokens / p.q_tiles);
-    if (bm == 256) return launch_one<8>(p, mode, stream);
-    if (bm == 128) return launch_one<4>(p, mode, stream);
-    return launch_one<2>(p, mode, stream);
+    if (f16) {
+        if (bm == 256) return launch_one<8, true>(p, mode, stream);
+        if (bm == 128) return launch_one<4, true>(p, mode, stream);
+        return launch_one<2, true>(p, mode, stream);
+    }
+    if (bm == 256) return launch_one<8, false>(p, mode, stream);
+    if (bm == 128) return launch_one<4, false>(p, mode, stream);
+    return launch_one<2, false>(p, mode, stream);
 }
 
 }  // namespace grat

@@ -73,11 +73,12 @@ int64_t longest_list(const Geometry& geo, int32_t ndim, grat_pattern pattern, co
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+bool is16(grat_dtype t) { return t == GRAT_BF16 || t == GRAT_F16; }   // the MFMA path's element types
 
 // O's strides when they are not Q's: same rules as in check_tensors.
 grat_status check_out_strides(grat_dtype dtype, int32_t head_dim, int64_t b, int64_t h, int64_t n) {
     if (n < head_dim || b < 0 || h < 0) return GRAT_ERR_BAD_DIMS;
-    const int vec = dtype == GRAT_BF16 ? 8 : 4;
+    const int vec = is16(dtype) ? 8 : 4;
     if (n % vec || b % vec || h % vec) return GRAT_ERR_UNSUPPORTED;
     if (n >= ((int64_t)1 << 24) || b >= ((int64_t)1 << 46) || h >= ((int64_t)1 << 46)) return GRAT_ERR_UNSUPPORTED;
     return GRAT_OK;
@@ -91,11 +92,11 @@ grat_status check_tensors(const void* Q, const void* K, const void* V, void* O, 
     if (batch < 1 || heads < 1 || head_dim < 1 || n_tokens < 1) return GRAT_ERR_BAD_DIMS;
     if (!(scale > 0.f) || !std::isfinite(scale)) return GRAT_ERR_BAD_DIMS;
     if (stride_n < head_dim || stride_b < 0 || stride_h < 0) return GRAT_ERR_BAD_DIMS;
-    if (dtype != GRAT_BF16 && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
-    if (dtype == GRAT_BF16 && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
+    if (!is16(dtype) && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
+    if (is16(dtype) && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
     if (dtype == GRAT_F32 && head_dim != 64 && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
     // rows are read and written as 16-byte vectors
-    const int vec = dtype == GRAT_BF16 ? 8 : 4;
+    const int vec = is16(dtype) ? 8 : 4;
     if (stride_n % vec || stride_b % vec || stride_h % vec) return GRAT_ERR_UNSUPPORTED;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return GRAT_ERR_UNSUPPORTED;
     // the token stride is kept in 32 bits (a 64-row tile then spans less than 4 GiB); the tensor
@@ -174,7 +175,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     if (ragged && n_global > 0) return GRAT_ERR_INDIVISIBLE;   // joint sequences: whole groups only
     if (max_kv < 1) return GRAT_ERR_BUFFER_TOO_SMALL;
     if (max_kv > kMaxListLen) return GRAT_ERR_UNSUPPORTED;
-    if (n_global > 0 && dtype != GRAT_BF16) return GRAT_ERR_UNSUPPORTED;
+    if (n_global > 0 && !is16(dtype)) return GRAT_ERR_UNSUPPORTED;
 
     AttnParams p{};
     p.Q = Q; p.K = K; p.V = V; p.O = O;
@@ -188,7 +189,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
 
     const int n_g = geo.group_tokens;
     int bm;   // query rows per workgroup
-    if (dtype == GRAT_BF16) {
+    if (is16(dtype)) {
         if (n_g % 64) return GRAT_ERR_UNSUPPORTED;
         // byte offsets inside one group are kept in 32 bits
         const int64_t span_rows = (int64_t)(geo.g[0] - 1) * geo.T[1] * geo.T[2] + (int64_t)(geo.g[1] - 1) * geo.T[2] + geo.g[2];
@@ -206,7 +207,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
 
     int mode = ragged ? 3 : 0;
     // the clipped-box tests of the bf16 kernel pack box coordinates into 12 + 10 + 10 bits
-    if (ragged && dtype == GRAT_BF16 && (geo.g[1] > 1024 || geo.g[2] > 1024)) return GRAT_ERR_UNSUPPORTED;
+    if (ragged && is16(dtype) && (geo.g[1] > 1024 || geo.g[2] > 1024)) return GRAT_ERR_UNSUPPORTED;
     if (n_global > 0) {   // joint sequence: prompt rows become dense tiles launched ahead of the rest
         mode = 2;
         p.n_global = n_global;
@@ -217,8 +218,8 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
         p.q_tiles_dense = (n_global + bm - 1) / bm;
         p.n_dense_tiles = batch * heads * p.q_tiles_dense;
     }
-    const hipError_t e = dtype == GRAT_BF16
-                             ? launch_attn_bf16(p, mode, (hipStream_t)hip_stream)
+    const hipError_t e = is16(dtype)
+                             ? launch_attn_bf16(p, mode, dtype == GRAT_F16, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, false, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }
@@ -256,14 +257,14 @@ extern "C" grat_status grat_attention_packed_fwd(const void* QKV, void* O, grat_
                                                  int32_t max_kv, void* hip_stream) {
     if (!QKV || !O) return GRAT_ERR_NULL;
     if (batch < 1 || heads < 1 || head_dim < 1) return GRAT_ERR_BAD_DIMS;
-    if (dtype != GRAT_BF16 && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
+    if (!is16(dtype) && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
     Geometry geo;
     const grat_status st = make_geometry(ndim, grid, group, &geo);
     if (st != GRAT_OK) return st;
     if (n_global < 0) return GRAT_ERR_BAD_DIMS;
     const int64_t seq_len = geo.n_tokens + n_global;
     const int64_t hd = (int64_t)heads * head_dim;            // one of Q, K, V of one token
-    const size_t esize = dtype == GRAT_BF16 ? 2 : 4;
+    const size_t esize = is16(dtype) ? 2 : 4;
     const char* base = (const char*)QKV;
     return attention_fwd(base, base + hd * esize, base + 2 * hd * esize, O, dtype, batch, heads,
                          head_dim, seq_len * 3 * hd, head_dim, 3 * hd,
@@ -288,7 +289,7 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     p.batch = batch; p.heads = heads;
     p.scale_log2 = scale * 1.4426950408889634f;
     p.n_tokens = (int32_t)n_tokens;
-    const int bm = dtype == GRAT_BF16 ? 256 : 64;
+    const int bm = is16(dtype) ? 256 : 64;
     p.q_tiles = (int32_t)((n_tokens + bm - 1) / bm);
     p.q_tiles_dense = p.q_tiles;
     p.n_dense_rows = (int32_t)n_tokens;
@@ -297,8 +298,8 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
-    const hipError_t e = dtype == GRAT_BF16
-                             ? launch_attn_bf16(p, 1, (hipStream_t)hip_stream)
+    const hipError_t e = is16(dtype)
+                             ? launch_attn_bf16(p, 1, dtype == GRAT_F16, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, true, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }

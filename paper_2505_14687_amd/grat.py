@@ -16,7 +16,7 @@ from .build import LIB_PATH
 
 GRAT_OK = 0
 PATTERNS = {"block": 0, "cross": 1, "cross_planes": 2, "dense": 3}
-DTYPES = {torch.bfloat16: 0, torch.float32: 1}
+DTYPES = {torch.bfloat16: 0, torch.float32: 1, torch.float16: 2}
 EXPORTS = ("grat_block_list_shape", "grat_build_block_lists", "grat_attention_fwd",
            "grat_attention_global_fwd", "grat_attention_packed_fwd", "grat_dense_attention_fwd",
            "grat_status_string")

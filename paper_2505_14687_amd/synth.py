@@ -91,16 +91,17 @@ def make_qkv(batch: int, heads: int, n: int, d: int, dtype: str, seed: int,
              q_gain: float = 1.0, threads: int = 8):
     """Q, K, V of shape [batch, heads, n, d].
 
-    dtype "f32": float32 arrays.  dtype "bf16": uint16 arrays of bf16 bit patterns.
+    dtype "f32": float32 arrays.  dtype "bf16": uint16 arrays of bf16 bit patterns.  dtype "f16":
+    float16 arrays (float32 rounded to nearest-even).
     q_gain scales Q before rounding (a gain of 4 makes the softmax peaked).
     """
-    out_dt = np.float32 if dtype == "f32" else np.uint16
+    out_dt = {"f32": np.float32, "bf16": np.uint16, "f16": np.float16}[dtype]
     out = [np.empty((batch, heads, n, d), dtype=out_dt) for _ in range(3)]
 
     def fill(job):
         t, b, h = job
         x = head_normal(seed, t, b, h, n, d, q_gain if t == 0 else 1.0)
-        out[t][b, h] = x if dtype == "f32" else f32_to_bf16_bits(x)
+        out[t][b, h] = f32_to_bf16_bits(x) if dtype == "bf16" else x   # (numpy rounds to float16 nearest-even)
 
     jobs = [(t, b, h) for t in range(3) for b in range(batch) for h in range(heads)]
     if threads > 1 and len(jobs) > 1:

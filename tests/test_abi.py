@@ -76,6 +76,7 @@ def test_attention_argument_errors_return_before_any_launch():
     assert call(grid=(2100, 64), group=(2048, 2)) == 6   # clipped border groups: box coordinates beyond the packing
     assert call(d=64) == 6                       # bf16 needs head_dim 128
     assert call(dtype=1, d=96) == 6
+    assert call(dtype=2, d=64) == 6              # half needs head_dim 128, too
     assert call(dtype=5) == 6
     assert call(group=(4, 4)) == 6               # 16-token groups on the bf16 path
     assert call(sn=132) == 6                     # rows not 16-byte aligned
