@@ -110,7 +110,7 @@ grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int3
  *                          [0, G) and every count in [1, max_kv]; the kernel does not check
  *                          them and an entry outside that range is undefined behaviour.
  * Supported (GRAT_ERR_UNSUPPORTED otherwise):
- *   GRAT_BF16, GRAT_F16: head_dim 128, tokens per (whole) group a multiple of 64; with clipped border
+ *   GRAT_BF16, GRAT_F16: head_dim 128 or 64, tokens per (whole) group a multiple of 64; with clipped border
  *              groups also group[k] <= 1024 on the last two axes;
  *   GRAT_F32 : head_dim 64 or 128, any group size;
  *   all      : N < 2^31 tokens, stride_n < 2^24 elements, max_kv <= 8192; 16-bit types also: the

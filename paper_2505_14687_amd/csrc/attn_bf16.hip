@@ -130,8 +130,16 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
     return (c >> 20) <= (lim >> 20) && ((c >> 10) & 1023u) <= ((lim >> 10) & 1023u) && (c & 1023u) <= (lim & 1023u);
 }
 
-template <int NWAVES, int MODE, bool F16>
+// D = head_dim of the tensors, 128 or 64.  The pipeline itself is 128 wide (kD): for D = 64 the LDS
+// tiles keep their 256-byte rows, are zeroed once, and the direct loads only fill the 8 chunk
+// positions of every row that belong to real head dims (the XOR swizzle is a bijection per row, so
+// the other 8 positions are the same in every tile and stay zero); the upper Q fragments are zero
+// and the upper half of O is never stored.  Half of the MFMA work is then spent on zeros - the
+// price of reusing one schedule; the softmax arithmetic, which bounds a 64-wide head anyway, is
+// the same per key.
+template <int NWAVES, int MODE, bool F16, int D>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
+    static_assert(D == 128 || D == 64, "head_dim 128 or 64");
     using E = Elem<F16>;
     constexpr int NT = NWAVES * 64;
     constexpr int BM = NWAVES * 32;
@@ -149,6 +157,13 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     const int half = lane >> 5;
 
     const Geometry& geo = p.geo;
+    if constexpr (D == 64) {   // the chunk positions the loads never write have to read as zero
+        for (int i = tid; i < 2 * kTileBytes / 16; i += NT) {
+            ((uint4*)&sK[0][0])[i] = make_uint4(0, 0, 0, 0);
+            ((uint4*)&sV[0][0])[i] = make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();
+    }
     int tile;             // index among the tiles of its kind
     bool dense;           // wave-uniform: this workgroup is a dense tile
     if (MODE == kJoint) {
@@ -236,7 +251,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             }
             const uint8_t* src = (const uint8_t*)Qh + (uint64_t)q_base * row_pitch + off + 16 * half;
 #pragma unroll
-            for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const frag8*)(src + 32 * ks);
+            for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = ks < D / 16 ? *(const frag8*)(src + 32 * ks) : frag8{0, 0, 0, 0, 0, 0, 0, 0};
         }
         for (int t = tid; t < n_g; t += NT) {
             const int c0 = t / g12, c1 = (t / geo.g[2]) % geo.g[1], c2 = t % geo.g[2];
@@ -271,7 +286,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     if (dense) {
         const uint8_t* src = (const uint8_t*)Qh + q_row_off(qcol) + 16 * half;
 #pragma unroll
-        for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = *(const frag8*)(src + 32 * ks);
+        for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = ks < D / 16 ? *(const frag8*)(src + 32 * ks) : frag8{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
     f32x16 oacc[kD / 32];                 // O^T accumulator: 4 blocks of 32 head dims
@@ -298,12 +313,15 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // the swizzled 16-byte chunk of the row.
     int load_row[LPW];
     uint32_t load_kcol[LPW], load_vcol[LPW];
+    bool k_on[LPW], v_on[LPW];
 #pragma unroll
     for (int k = 0; k < LPW; ++k) {
         const int row = 4 * (wave * LPW + k) + (lane >> 4);
         load_row[k] = row;
         load_kcol[k] = (uint32_t)(((lane & 15) ^ k_swizzle(row)) * 16);   // byte offset of the global chunk
         load_vcol[k] = (uint32_t)(((lane & 15) ^ v_swizzle(row)) * 16);
+        k_on[k] = load_kcol[k] < (uint32_t)D * 2;   // D = 64: this lane's LDS position holds a real chunk
+        v_on[k] = load_vcol[k] < (uint32_t)D * 2;
     }
     struct TileAddr {
         uint32_t base;        // wave-uniform
@@ -338,7 +356,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // direct-to-LDS load it can see as a possible alias of every later LDS read and would drain
     // the prefetch before the first fragment read that follows.  Completion is waited for
     // explicitly (s_waitcnt vmcnt(0)) before the barrier that publishes the tile.
-    auto issue_tile = [&](const uint16_t* head, uint8_t* dst_tile, const TileAddr& a) {
+    auto issue_tile = [&](const uint16_t* head, uint8_t* dst_tile, const TileAddr& a, const bool (&on)[LPW]) {
         // (made uniform again here: carried across iterations the offset may sit in a vector register)
         const uint8_t* base = (const uint8_t*)head + (uint64_t)__builtin_amdgcn_readfirstlane(a.base) * row_pitch;
 #pragma unroll
@@ -347,8 +365,9 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             const uint32_t lds_dst = __builtin_amdgcn_readfirstlane(
                 (uint32_t)(uintptr_t)(LDS_PTR(uint8_t))(dst_tile + (wave * LPW + k) * 1024));
             // (one wait state between the M0 write and the LDS-DMA instruction that reads it)
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(lds_dst), "v"(a.off[k]), "s"(base) : "memory", "m0");
+            if (D == 128 || on[k])
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :: "s"(lds_dst), "v"(a.off[k]), "s"(base) : "memory", "m0");
         }
     };
 
@@ -495,7 +514,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 
     // ---- prologue: K tile 0 -----------------------------------------------------------------
     tile_addr(ka, load_kcol, 0, gi_k, j_k);
-    issue_tile(Kh, sK[0], ka);
+    issue_tile(Kh, sK[0], ka, k_on);
     if (1 < n_tiles) tile_addr(ka, load_kcol, 1, gi_k, j_k);
     tile_addr(va, load_vcol, 0, gi_v, j_v);
 
@@ -504,8 +523,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     auto swap_barrier = [&](int t) {
         __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
-        if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka);
-        if (t < n_tiles) issue_tile(Vh, sV[t & 1], va);
+        if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka, k_on);
+        if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
         // (grouped: looked up unconditionally, so that the table reads stay inside the straight-line
         // block that follows instead of becoming a block of their own with its own waits)
         if (kLists || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
@@ -581,7 +600,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         }
         uint8_t* wr = stage + qcol * 128 + 8 * half;
 #pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
+        for (int pass = 0; pass < D / 64; ++pass) {
 #pragma unroll
             for (int dbp = 0; dbp < 2; ++dbp)
 #pragma unroll
@@ -604,35 +623,36 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     }
 }
 
-template <int NWAVES, bool F16>
+template <int NWAVES, bool F16, int D>
 static hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
     const dim3 block(NWAVES * 64);
     const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * (mode == kRagged ? 2 : 1) * ((size_t)p.geo.group_tokens + p.max_kv);
     if (mode == kRagged) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kRagged, F16>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kRagged, F16, D>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else if (mode == kDense) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense, F16>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense, F16, D>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else if (mode == kGrouped) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped, F16>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped, F16, D>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
     } else {
         const int blocks = xcd_padded_blocks(p.n_dense_tiles) + xcd_padded_blocks(p.total_tiles);
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kJoint, F16>), dim3(blocks), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
     }
     return hipGetLastError();
 }
 
+template <bool F16, int D>
+static hipError_t launch_by_tile(const AttnParams& p, int mode, hipStream_t stream) {
+    const int bm = mode == kDense ? 256 : (p.geo.group_tokens / p.q_tiles);
+    if (bm == 256) return launch_one<8, F16, D>(p, mode, stream);
+    if (bm == 128) return launch_one<4, F16, D>(p, mode, stream);
+    return launch_one<2, F16, D>(p, mode, stream);
+}
+
 // The host computed p.q_tiles (and p.q_tiles_dense) for the query-tile height chosen here:
 // 256, 128 or 64 rows.  f16: the elements are IEEE half instead of bfloat16.
-hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, hipStream_t stream) {
-    const int bm = mode == kDense ? 256 : (p.geo.group_tokens / p.q_tiles);
-    if (f16) {
-        if (bm == 256) return launch_one<8, true>(p, mode, stream);
-        if (bm == 128) return launch_one<4, true>(p, mode, stream);
-        return launch_one<2, true>(p, mode, stream);
-    }
-    if (bm == 256) return launch_one<8, false>(p, mode, stream);
-    if (bm == 128) return launch_one<4, false>(p, mode, stream);
-    return launch_one<2, false>(p, mode, stream);
+hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, int head_dim, hipStream_t stream) {
+    if (head_dim == 64) return f16 ? launch_by_tile<true, 64>(p, mode, stream) : launch_by_tile<false, 64>(p, mode, stream);
+    return f16 ? launch_by_tile<true, 128>(p, mode, stream) : launch_by_tile<false, 128>(p, mode, stream);
 }
 
 }  // namespace grat

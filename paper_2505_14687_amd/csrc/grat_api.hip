@@ -93,7 +93,7 @@ grat_status check_tensors(const void* Q, const void* K, const void* V, void* O, 
     if (!(scale > 0.f) || !std::isfinite(scale)) return GRAT_ERR_BAD_DIMS;
     if (stride_n < head_dim || stride_b < 0 || stride_h < 0) return GRAT_ERR_BAD_DIMS;
     if (!is16(dtype) && dtype != GRAT_F32) return GRAT_ERR_UNSUPPORTED;
-    if (is16(dtype) && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
+    if (is16(dtype) && head_dim != 64 && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
     if (dtype == GRAT_F32 && head_dim != 64 && head_dim != 128) return GRAT_ERR_UNSUPPORTED;
     // rows are read and written as 16-byte vectors
     const int vec = is16(dtype) ? 8 : 4;
@@ -219,7 +219,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
         p.n_dense_tiles = batch * heads * p.q_tiles_dense;
     }
     const hipError_t e = is16(dtype)
-                             ? launch_attn_bf16(p, mode, dtype == GRAT_F16, (hipStream_t)hip_stream)
+                             ? launch_attn_bf16(p, mode, dtype == GRAT_F16, head_dim, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, false, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }
@@ -299,7 +299,7 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     p.total_tiles = (int32_t)total;
 
     const hipError_t e = is16(dtype)
-                             ? launch_attn_bf16(p, 1, dtype == GRAT_F16, (hipStream_t)hip_stream)
+                             ? launch_attn_bf16(p, 1, dtype == GRAT_F16, head_dim, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, true, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }

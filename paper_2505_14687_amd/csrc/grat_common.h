@@ -52,7 +52,7 @@ hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern 
                                     const int32_t radius[3], int32_t* d_kv_count,
                                     int32_t* d_kv_index, int32_t max_kv, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, bool dense, hipStream_t stream);
-hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, hipStream_t stream);   // mode: 0 grouped, 1 dense, 2 joint, 3 grouped with clipped border groups
+hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, int head_dim, hipStream_t stream);   // mode: 0 grouped, 1 dense, 2 joint, 3 grouped with clipped border groups
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
 // contiguous range of the logical tile order instead, so that tiles sharing K/V meet in one L2.

@@ -74,9 +74,9 @@ def test_attention_argument_errors_return_before_any_launch():
     assert call(batch=0) == 2 and call(scale=0.0) == 2 and call(scale=float("nan")) == 2
     assert call(sn=64) == 2
     assert call(grid=(2100, 64), group=(2048, 2)) == 6   # clipped border groups: box coordinates beyond the packing
-    assert call(d=64) == 6                       # bf16 needs head_dim 128
+    assert call(d=96) == 6                       # the 16-bit path has head_dim 128 or 64
     assert call(dtype=1, d=96) == 6
-    assert call(dtype=2, d=64) == 6              # half needs head_dim 128, too
+    assert call(dtype=2, d=32) == 6
     assert call(dtype=5) == 6
     assert call(group=(4, 4)) == 6               # 16-token groups on the bf16 path
     assert call(sn=132) == 6                     # rows not 16-byte aligned
@@ -126,7 +126,7 @@ def test_packed_entry_argument_errors():
                                            i32x2(*group), cnt, fake, max_kv, None)
     assert call(QKV=None) == 1 and call(O=None) == 1 and call(cnt=None) == 1
     assert call(heads=0) == 2 and call(n_global=-1) == 2
-    assert call(dtype=3) == 6 and call(d=64) == 6
+    assert call(dtype=3) == 6 and call(d=96) == 6
     assert call(dtype=1, n_global=8) == 6
     assert call(grid=(64, 60), n_global=8) == 3    # prompt tokens: whole groups only
     assert call(QKV=fake + 4) == 6                 # not 16-byte aligned
