@@ -1,4 +1,5 @@
-// bf16 block-sparse flash attention for gfx950 (grouped and dense), head_dim 128.
+// Block-sparse flash attention on the matrix cores of gfx950 (grouped, dense, joint), bf16 or half,
+// head_dim 128 or 64.  The kernel template; its instantiations are compiled in attn_mfma_*.hip.
 //
 // Computes Sec. 3.1 Eq. 1 restricted to the attendable KV groups of Sec. 3.2.  Because all
 // queries of a group share one KV list, every (query tile, KV tile) product is a full dense
@@ -29,6 +30,7 @@
 // (P is double buffered, PV lags QK by a tile), so each stretch of vector-ALU work has
 // independent MFMAs of the same wave to hide behind, and the two waves of a SIMD fill each
 // other's remaining gaps.
+#pragma once
 #include "grat_common.h"
 
 namespace grat {
@@ -624,7 +626,7 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
 }
 
 template <int NWAVES, bool F16, int D>
-static hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
+inline hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
     const dim3 block(NWAVES * 64);
     const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * (mode == kRagged ? 2 : 1) * ((size_t)p.geo.group_tokens + p.max_kv);
     if (mode == kRagged) {
@@ -640,19 +642,14 @@ static hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) 
     return hipGetLastError();
 }
 
+// p.q_tiles (and p.q_tiles_dense) were computed by the host for the query-tile height chosen here:
+// 256, 128 or 64 rows.
 template <bool F16, int D>
-static hipError_t launch_by_tile(const AttnParams& p, int mode, hipStream_t stream) {
+inline hipError_t launch_by_tile(const AttnParams& p, int mode, hipStream_t stream) {
     const int bm = mode == kDense ? 256 : (p.geo.group_tokens / p.q_tiles);
     if (bm == 256) return launch_one<8, F16, D>(p, mode, stream);
     if (bm == 128) return launch_one<4, F16, D>(p, mode, stream);
     return launch_one<2, F16, D>(p, mode, stream);
-}
-
-// The host computed p.q_tiles (and p.q_tiles_dense) for the query-tile height chosen here:
-// 256, 128 or 64 rows.  f16: the elements are IEEE half instead of bfloat16.
-hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, int head_dim, hipStream_t stream) {
-    if (head_dim == 64) return f16 ? launch_by_tile<true, 64>(p, mode, stream) : launch_by_tile<false, 64>(p, mode, stream);
-    return f16 ? launch_by_tile<true, 128>(p, mode, stream) : launch_by_tile<false, 128>(p, mode, stream);
 }
 
 }  // namespace grat
