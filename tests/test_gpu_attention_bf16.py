@@ -258,3 +258,26 @@ def test_caller_supplied_lists():
     want = np.stack([orc.masked_attention(host[0][0, h], host[1][0, h], host[2][0, h], mask, 0.09)
                      for h in range(2)])[None]
     assert_close(to_f64(O), want, "bf16", "hand-made lists")
+
+
+# ---- the largest sizes the entry points accept --------------------------------------------------
+def test_longest_list_8192_groups():
+    """max_kv = 8192 (the limit): a 1D sequence of 8192 groups of 64 tokens, every group listed."""
+    grid, group = (8192 * 64,), (64,)
+    host = synth.make_qkv(1, 1, grid[0], 128, "bf16", 96, threads=8)
+    dev = [to_device(x) for x in host]
+    scale = 1.0 / math.sqrt(128)
+    count, index = grat.grat_build_block_lists(grid, group, "dense")
+    assert index.shape == (8192, 8192) and int(count.min()) == 8192
+    O = grat.grat_attention_fwd(*dev, scale, grid, group, count, index)
+    torch.cuda.synchronize()
+    samples = synth.sample_rows(2012, 48, 1, 1, grid[0])
+    samples[:2, 2] = [0, grid[0] - 1]
+    want = orc.dense_attention_rows(*host, samples, scale)
+    print(assert_close(gather_rows(O, samples), want, "bf16", "8192-entry lists"))
+
+
+def test_largest_group_4096_tokens():
+    """4096 tokens per group (the limit of the in-LDS offset table): 16 query tiles per group."""
+    got, want = small_case(1, 2, (128, 64), (64, 64), "block", (1, 0), seed=97)
+    assert_close(got, want, "bf16", "4096-token groups")
