@@ -111,17 +111,7 @@ __device__ __forceinline__ float sum_across_halves(float x) {
     return lo + hi;
 }
 
-// MODE: what a workgroup can be.
-//   kGrouped  every workgroup is a query tile of one group and walks that group's KV list;
-//   kDense    every workgroup is a tile of consecutive query rows and walks all KV tiles;
-//   kJoint    joint sequence of prompt tokens and grid tokens: the first p.n_dense_tiles tiles are
-//             dense tiles over the prompt rows (they attend the whole sequence), the others are
-//             grouped tiles whose walk starts with the prompt tokens' KV tiles.
-//   kRagged   kGrouped for a grid the group dims do not divide (Eq. 2-4 are floor divisions): a
-//             group at the far border is the part of its box inside the grid.  Boxes are still
-//             walked whole; tokens of a box that fall outside the grid are fetched from a clamped
-//             (valid, meaningless) address and get weight 0, queries outside are not stored.
-enum : int { kGrouped = 0, kDense = 1, kJoint = 2, kRagged = 3 };
+// (MODE: see AttnMode in grat_common.h)
 
 // Box coordinates of an intra-group token, packed for the border tests of kRagged: 12 + 10 + 10 bits.
 __device__ __forceinline__ uint32_t pack_coord(int c0, int c1, int c2) {

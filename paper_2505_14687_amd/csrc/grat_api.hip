@@ -147,9 +147,16 @@ extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid,
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }
 
-// Shared by grat_attention_fwd (n_global = 0) and grat_attention_global_fwd.
 struct OutStrides { int64_t b, h, n; };   // O's own strides (elements)
 
+// LDS the MFMA kernel needs beside its four 16-KiB tiles: the row-offset table of a group and the
+// list's group origins, twice that with clipped border groups (box coordinates, in-grid limits).
+static bool tables_fit_lds(const Geometry& geo, int32_t max_kv, bool ragged) {
+    const int64_t tables = (ragged ? 2 : 1) * ((int64_t)geo.group_tokens + max_kv) * (int64_t)sizeof(int32_t);
+    return 4 * 16384 + tables <= 160 * 1024;
+}
+
+// Shared by grat_attention_fwd (n_global = 0), grat_attention_global_fwd and grat_attention_packed_fwd.
 static grat_status attention_fwd(const void* Q, const void* K, const void* V, void* O,
                                  grat_dtype dtype, int32_t batch, int32_t heads, int32_t head_dim,
                                  int64_t stride_b, int64_t stride_h, int64_t stride_n,
@@ -195,6 +202,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
         const int64_t span_rows = (int64_t)(geo.g[0] - 1) * geo.T[1] * geo.T[2] + (int64_t)(geo.g[1] - 1) * geo.T[2] + geo.g[2];
         if (span_rows * stride_n * 2 >= ((int64_t)1 << 32)) return GRAT_ERR_UNSUPPORTED;
         if (n_g > 4096) return GRAT_ERR_UNSUPPORTED;   // intra-group offset table lives in LDS
+        if (!tables_fit_lds(geo, max_kv, ragged)) return GRAT_ERR_UNSUPPORTED;
         bm = n_g % 256 == 0 ? 256 : (n_g % 128 == 0 ? 128 : 64);
     } else {
         bm = 64;
@@ -205,11 +213,11 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
-    int mode = ragged ? 3 : 0;
+    int mode = ragged ? kRagged : kGrouped;
     // the clipped-box tests of the bf16 kernel pack box coordinates into 12 + 10 + 10 bits
     if (ragged && is16(dtype) && (geo.g[1] > 1024 || geo.g[2] > 1024)) return GRAT_ERR_UNSUPPORTED;
     if (n_global > 0) {   // joint sequence: prompt rows become dense tiles launched ahead of the rest
-        mode = 2;
+        mode = kJoint;
         p.n_global = n_global;
         p.global_row0 = global_first ? 0 : (int32_t)geo.n_tokens;
         p.grid_row0 = global_first ? n_global : 0;
@@ -299,7 +307,7 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     p.total_tiles = (int32_t)total;
 
     const hipError_t e = is16(dtype)
-                             ? launch_attn_bf16(p, 1, dtype == GRAT_F16, head_dim, (hipStream_t)hip_stream)
+                             ? launch_attn_bf16(p, kDense, dtype == GRAT_F16, head_dim, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, true, (hipStream_t)hip_stream);
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }

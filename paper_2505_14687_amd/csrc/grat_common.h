@@ -47,12 +47,24 @@ struct AttnParams {
     int32_t grid_row0;         // first grid row
 };
 
+// What a workgroup of the MFMA attention kernel can be (its MODE template argument).
+//   kGrouped  every workgroup is a query tile of one group and walks that group's KV list;
+//   kDense    every workgroup is a tile of consecutive query rows and walks all KV tiles;
+//   kJoint    joint sequence of prompt tokens and grid tokens: the first p.n_dense_tiles tiles are
+//             dense tiles over the prompt rows (they attend the whole sequence), the others are
+//             grouped tiles whose walk starts with the prompt tokens' KV tiles.
+//   kRagged   kGrouped for a grid the group dims do not divide (Eq. 2-4 are floor divisions): a
+//             group at the far border is the part of its box inside the grid.  Boxes are still
+//             walked whole; tokens of a box that fall outside the grid are fetched from a clamped
+//             (valid, meaningless) address and get weight 0, queries outside are not stored.
+enum AttnMode : int { kGrouped = 0, kDense = 1, kJoint = 2, kRagged = 3 };
+
 // Launchers: each returns the hipError_t of its launch.
 hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern pattern,
                                     const int32_t radius[3], int32_t* d_kv_count,
                                     int32_t* d_kv_index, int32_t max_kv, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, bool dense, hipStream_t stream);
-hipError_t launch_attn_bf16(const AttnParams& p, int mode, bool f16, int head_dim, hipStream_t stream);   // mode: 0 grouped, 1 dense, 2 joint, 3 grouped with clipped border groups
+hipError_t launch_attn_bf16(const AttnParams& p, int mode /* AttnMode */, bool f16, int head_dim, hipStream_t stream);
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
 // contiguous range of the logical tile order instead, so that tiles sharing K/V meet in one L2.
