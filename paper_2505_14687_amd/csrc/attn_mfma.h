@@ -122,13 +122,12 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
     return (c >> 20) <= (lim >> 20) && ((c >> 10) & 1023u) <= ((lim >> 10) & 1023u) && (c & 1023u) <= (lim & 1023u);
 }
 
-// D = head_dim of the tensors, 128 or 64.  The pipeline itself is 128 wide (kD): for D = 64 the LDS
-// tiles keep their 256-byte rows, are zeroed once, and the direct loads only fill the 8 chunk
-// positions of every row that belong to real head dims (the XOR swizzle is a bijection per row, so
-// the other 8 positions are the same in every tile and stay zero); the upper Q fragments are zero
-// and the upper half of O is never stored.  Half of the MFMA work is then spent on zeros - the
-// price of reusing one schedule; the softmax arithmetic, which bounds a 64-wide head anyway, is
-// the same per key.
+// D = head_dim of the tensors, 128 or 64.  The LDS layout is 128 wide (kD) either way: for D = 64
+// the tiles keep their 256-byte rows, same swizzles, same fragment addresses; the direct loads
+// only fill the 8 chunk positions of every row that belong to real head dims (lanes whose
+// position would hold a chunk that does not exist are masked off), the QK product contracts over
+// the 4 fragments that exist, and the upper half of O^T is never formed, so no MFMA or LDS read is
+// spent on padding (the unused chunk positions are never written and never read).
 template <int NWAVES, int MODE, bool F16, int D>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
     static_assert(D == 128 || D == 64, "head_dim 128 or 64");
@@ -149,13 +148,6 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     const int half = lane >> 5;
 
     const Geometry& geo = p.geo;
-    if constexpr (D == 64) {   // the chunk positions the loads never write have to read as zero
-        for (int i = tid; i < 2 * kTileBytes / 16; i += NT) {
-            ((uint4*)&sK[0][0])[i] = make_uint4(0, 0, 0, 0);
-            ((uint4*)&sV[0][0])[i] = make_uint4(0, 0, 0, 0);
-        }
-        __syncthreads();
-    }
     int tile;             // index among the tiles of its kind
     bool dense;           // wave-uniform: this workgroup is a dense tile
     if (MODE == kJoint) {
@@ -373,11 +365,11 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // chunk = 4*db + 2*dsel + cq/2, swizzled with 4*(row & 3) = 4*e  ->  4*(db ^ e) + 2*dsel + cq/2
     const int v_chunk_lo = 2 * tr_dsel + (tr_cq >> 1);
 
-    // QK for the 32-key block kb of the tile in sK[kbuf]: 8 fragment reads, 8 MFMAs
+    // QK for the 32-key block kb of the tile in sK[kbuf]: D/16 fragment reads and MFMAs
     auto qk_half = [&](int kbuf, int kb) {
         const uint8_t* kt = sK[kbuf] + k_lane_base + kb * 32 * kRowBytes;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < D / 64; ++j) {   // 16 head dims per fragment, 4 fragments at a time
             frag8 f[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) f[i] = *(const frag8*)(kt + (((2 * (4 * j + i)) ^ k_x) << 4));
