@@ -210,7 +210,9 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
                      "traffic": None if n_glob else measured_traffic(args.workload, args.pattern),
-                     "kernel": "grat::attn_bf16_kernel (grouped mode%s)" % (" + prompt tokens" if n_glob else ""),
+                     # template arguments: waves per workgroup, mode (0 grouped, 2 joint), half?, head_dim
+                     "kernel": "grat::attn_bf16_kernel<%d, %d, false, %d>" % (
+                         8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
                      "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4)},
         "cpu_baseline": cpu,
         "dense": dense,
