@@ -25,6 +25,9 @@ def pack(dev):
     ("bf16", 128, (32, 48), (8, 8), "block", (1, 1), 0),           # 2-wave workgroups
     ("bf16", 128, (4, 16, 16), (4, 8, 8), "cross_planes", (0, 0, 0), 0),
     ("bf16", 128, (32, 32), (16, 16), "block", (1, 1), 100),       # prompt tokens ahead of the grid
+    ("bf16", 128, (40, 56), (16, 16), "block", (1, 1), 0),         # clipped border groups, O with its own pitch
+    ("f16", 64, (33, 47), (8, 8), "cross", (0, 0), 0),             # half, head_dim 64, clipped, 2-wave workgroups
+    ("f32", 64, (30, 44), (8, 8), "block", (1, 1), 0),             # fp32 path, clipped
     ("f32", 64, (32, 32), (8, 8), "block", (1, 1), 0),
     ("f32", 128, (24, 40), (4, 8), "cross", (0, 0), 0),
 ])
