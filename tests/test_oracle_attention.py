@@ -217,6 +217,23 @@ def test_bf16_bits_decode_exactly():
     np.testing.assert_array_equal(O1, O2)
 
 
+def test_half_inputs_are_read_exactly():
+    """float16 inputs: the generator rounds float32 to nearest-even (checked against torch's
+    conversion) and the oracle works on exactly those values."""
+    x = np.array([0.0, 1.0, -2.5, 3.140625, 1e-3, 0.1, 65504.0, 6.1e-5, 2049.0], dtype=np.float32)
+    h = x.astype(np.float16)
+    t = torch.from_numpy(x).to(torch.float16)
+    assert (h.view(np.int16) == t.view(torch.int16).numpy()).all()
+    Qh, Kh, Vh = synth.make_qkv(1, 1, 64, 8, "f16", 5)
+    assert Qh.dtype == np.float16
+    ref = synth.head_normal(5, 0, 0, 0, 64, 8)
+    assert (Qh[0, 0].view(np.int16) == torch.from_numpy(ref).to(torch.float16).view(torch.int16).numpy()).all()
+    O1 = orc.grat_attention(Qh, Kh, Vh, (8, 8), (4, 4), "block", (0, 0), 0.3)
+    O2 = orc.grat_attention(Qh.astype(np.float64), Kh.astype(np.float64), Vh.astype(np.float64),
+                            (8, 8), (4, 4), "block", (0, 0), 0.3)
+    np.testing.assert_array_equal(O1, O2)
+
+
 def test_synth_is_seeded_and_per_head():
     w = synth.WORKLOADS["tiny2d"]
     Q1, K1, V1 = synth.make_workload_qkv(w)
