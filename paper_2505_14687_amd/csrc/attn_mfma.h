@@ -31,6 +31,8 @@
 // independent MFMAs of the same wave to hide behind, and the two waves of a SIMD fill each
 // other's remaining gaps.
 #pragma once
+#include <type_traits>
+
 #include "grat_common.h"
 
 namespace grat {
@@ -128,18 +130,23 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
 // position would hold a chunk that does not exist are masked off), the QK product contracts over
 // the 4 fragments that exist, and the upper half of O^T is never formed, so no MFMA or LDS read is
 // spent on padding (the unused chunk positions are never written and never read).
-template <int NWAVES, int MODE, bool F16, int D>
-__global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
+//
+// One query tile.  `tile` = its index among the tiles of its kind; DENSE: it is a tile of consecutive
+// query rows that walks the whole sequence (always in kDense, the prompt rows in kJoint), else a
+// tile of one query group.  sK / sV: the workgroup's two K and two V tile buffers in LDS.
+template <int NWAVES, int MODE, bool F16, int D, bool DENSE>
+__device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, uint8_t (*sK)[kTileBytes],
+                                          uint8_t (*sV)[kTileBytes]) {
     static_assert(D == 128 || D == 64, "head_dim 128 or 64");
     using E = Elem<F16>;
     constexpr int NT = NWAVES * 64;
     constexpr int BM = NWAVES * 32;
     constexpr int LPW = 16 / NWAVES;   // 1-KiB direct loads per wave per 16-KiB tile
+    constexpr bool dense = DENSE;
 
-    __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
     extern __shared__ int32_t s_dyn[];   // [n_g] row offsets inside a group, then [max_kv] group origins (kRagged: and the two tables below)
     constexpr bool kLists = MODE == kGrouped || MODE == kRagged;   // every KV tile comes from a listed group
+    constexpr bool kLeadThenLists = MODE == kJoint && !DENSE;      // prompt tiles first, then the listed groups
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -148,27 +155,6 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     const int half = lane >> 5;
 
     const Geometry& geo = p.geo;
-    int tile;             // index among the tiles of its kind
-    bool dense;           // wave-uniform: this workgroup is a dense tile
-    if (MODE == kJoint) {
-        // The long-running dense tiles get the lowest block indices, dealt round-robin over the
-        // XCDs; behind them every XCD walks its contiguous range of grouped tiles.
-        const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
-        const int dense_per_xcd = (p.n_dense_tiles + kNumXcd - 1) / kNumXcd;
-        dense = idx < dense_per_xcd;
-        if (dense) {
-            tile = idx * kNumXcd + xcd;
-            if (tile >= p.n_dense_tiles) return;
-        } else {
-            const int per = (p.total_tiles + kNumXcd - 1) / kNumXcd;
-            tile = xcd * per + (idx - dense_per_xcd);
-            if (idx - dense_per_xcd >= per || tile >= p.total_tiles) return;
-        }
-    } else {
-        dense = MODE == kDense;
-        tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
-        if (tile >= p.total_tiles) return;
-    }
     const int tiles_per_head = dense ? p.q_tiles_dense : geo.num_groups * p.q_tiles;
     const int bh = tile / tiles_per_head;
     const int t_in_head = tile % tiles_per_head;
@@ -316,13 +302,25 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     // Offsets of a tile are looked up one tile before it is fetched, so the table reads never sit
     // between a barrier and the loads that follow it.
     auto tile_addr = [&](TileAddr& a, const uint32_t* col, int t, int& gi, int& j) {
-        if (!kLists && (dense || t < n_lead)) {
-            // consecutive rows: the whole sequence (dense tile) or the prompt tokens (leading tiles)
-            const int first = dense ? 0 : p.global_row0, count = dense ? p.n_tokens : p.n_global;
-            a.base = (uint32_t)(first + t * kBN);
+        if (dense) {
+            // consecutive rows of the whole sequence; rows past the end re-read the last token (masked later)
+            a.base = (uint32_t)(t * kBN);
 #pragma unroll
-            for (int k = 0; k < LPW; ++k)   // rows past the end re-read the last token (masked later)
-                a.off[k] = (uint32_t)min(load_row[k], count - 1 - t * kBN) * row_pitch + col[k];
+            for (int k = 0; k < LPW; ++k)
+                a.off[k] = (uint32_t)min(load_row[k], p.n_tokens - 1 - t * kBN) * row_pitch + col[k];
+        } else if (kLeadThenLists) {
+            // Both kinds of address are formed every time and one is selected, so that there is no
+            // branch (and no block of table reads with waits of its own) inside a step.
+            const bool lead = t < n_lead;
+            const uint32_t base_list = __builtin_amdgcn_readfirstlane(s_origin[min(gi, n_listed - 1)]);
+            a.base = lead ? (uint32_t)(p.global_row0 + t * kBN) : base_list;
+#pragma unroll
+            for (int k = 0; k < LPW; ++k) {
+                const uint32_t o_list = s_rowbytes[j * kBN + load_row[k]];
+                const uint32_t o_lead = (uint32_t)max(0, min(load_row[k], p.n_global - 1 - t * kBN)) * row_pitch;
+                a.off[k] = (lead ? o_lead : o_list) + col[k];
+            }
+            if (!lead && ++j == tiles_per_group) { j = 0; ++gi; }
         } else {
             a.base = __builtin_amdgcn_readfirstlane(s_origin[min(gi, n_listed - 1)]);   // (may be asked past the end)
             // kRagged: rows of the box beyond the last token of the sequence are pulled back onto it
@@ -511,8 +509,8 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
         // (grouped: looked up unconditionally, so that the table reads stay inside the straight-line
         // block that follows instead of becoming a block of their own with its own waits)
-        if (kLists || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
-        if (kLists || t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
+        if (kLists || kLeadThenLists || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
+        if (kLists || kLeadThenLists || t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
 
     // tile 0: QK and weights only
@@ -526,12 +524,16 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
     }
     // tile t >= 1: QK(t), weights(t) and PV(t-1) in one straight-line block; the statement order
     // below is only a hint, the instruction scheduler interleaves the three streams
-    auto tile_step = [&](int t, uint32_t (&pw_cur)[2][8], const uint32_t (&pw_prev)[2][8]) {
+    // (check: a compile-time flag - the walk contains a tile with fewer than 64 valid keys.  Without
+    // it the step is one basic block; the test for that tile would split it after the QK product.)
+    auto tile_step = [&](auto check, int t, uint32_t (&pw_cur)[2][8], const uint32_t (&pw_prev)[2][8]) {
         swap_barrier(t);
         float ls = 0.f;
         qk_half(t & 1, 0);
         qk_half(t & 1, 1);
-        if (!kLists && t == mask_tile) mask_tail();
+        if constexpr (decltype(check)::value) {
+            if (t == mask_tile) mask_tail();
+        }
         if (MODE == kRagged) mask_outside();
         exp_half(0, pw_cur, ls);
         pv_half((t - 1) & 1, 0, pw_prev);
@@ -539,21 +541,25 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
         pv_half((t - 1) & 1, 1, pw_prev);
         finish_softmax(pw_cur, ls);
     };
-    int t = 1;
-    for (; t + 1 < n_tiles; t += 2) {
-        tile_step(t, pwB, pwA);
-        tile_step(t + 1, pwA, pwB);
-    }
-    if (t < n_tiles) {
-        tile_step(t, pwB, pwA);
-        swap_barrier(n_tiles);
-        pv_half((n_tiles - 1) & 1, 0, pwB);
-        pv_half((n_tiles - 1) & 1, 1, pwB);
-    } else {
-        swap_barrier(n_tiles);
-        pv_half((n_tiles - 1) & 1, 0, pwA);
-        pv_half((n_tiles - 1) & 1, 1, pwA);
-    }
+    auto walk = [&](auto check) {
+        int t = 1;
+        for (; t + 1 < n_tiles; t += 2) {
+            tile_step(check, t, pwB, pwA);
+            tile_step(check, t + 1, pwA, pwB);
+        }
+        if (t < n_tiles) {
+            tile_step(check, t, pwB, pwA);
+            swap_barrier(n_tiles);
+            pv_half((n_tiles - 1) & 1, 0, pwB);
+            pv_half((n_tiles - 1) & 1, 1, pwB);
+        } else {
+            swap_barrier(n_tiles);
+            pv_half((n_tiles - 1) & 1, 0, pwA);
+            pv_half((n_tiles - 1) & 1, 1, pwA);
+        }
+    };
+    if (!kLists && mask_tile >= 1) walk(std::true_type{});   // (tile 0 was handled above)
+    else walk(std::false_type{});
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
     // In the accumulator layout a lane holds 4 consecutive head dims (8 bytes) at a time of ITS
@@ -604,6 +610,31 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p)
             }
             __builtin_amdgcn_wave_barrier();   // (... and the next pass's writes below these reads)
         }
+    }
+}
+
+// The kernel: picks this workgroup's query tile and runs it.  Tiles are handed out so that every
+// XCD works through one contiguous range of the tile order (see xcd_contiguous_tile); in joint
+// mode the long-running dense tiles over the prompt rows get the lowest block indices, dealt
+// round-robin over the XCDs, and behind them every XCD walks its range of grouped tiles.
+template <int NWAVES, int MODE, bool F16, int D>
+__global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
+    __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
+    if constexpr (MODE == kJoint) {
+        const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
+        const int dense_per_xcd = (p.n_dense_tiles + kNumXcd - 1) / kNumXcd;
+        if (idx < dense_per_xcd) {
+            const int tile = idx * kNumXcd + xcd;
+            if (tile < p.n_dense_tiles) attn_tile<NWAVES, MODE, F16, D, true>(p, tile, sK, sV);
+        } else {
+            const int per = (p.total_tiles + kNumXcd - 1) / kNumXcd;
+            const int tile = xcd * per + (idx - dense_per_xcd);
+            if (idx - dense_per_xcd < per && tile < p.total_tiles) attn_tile<NWAVES, MODE, F16, D, false>(p, tile, sK, sV);
+        }
+    } else {
+        const int tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
+        if (tile < p.total_tiles) attn_tile<NWAVES, MODE, F16, D, MODE == kDense>(p, tile, sK, sV);
     }
 }
 
