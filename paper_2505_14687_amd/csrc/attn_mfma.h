@@ -306,8 +306,8 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
             // consecutive rows of the whole sequence; rows past the end re-read the last token (masked later)
             a.base = (uint32_t)(t * kBN);
 #pragma unroll
-            for (int k = 0; k < LPW; ++k)
-                a.off[k] = (uint32_t)min(load_row[k], p.n_tokens - 1 - t * kBN) * row_pitch + col[k];
+            for (int k = 0; k < LPW; ++k)   // (also asked for tiles past the end, never fetched: keep the offset small)
+                a.off[k] = (uint32_t)max(0, min(load_row[k], p.n_tokens - 1 - t * kBN)) * row_pitch + col[k];
         } else if (kLeadThenLists) {
             // Both kinds of address are formed every time and one is selected, so that there is no
             // branch (and no block of table reads with waits of its own) inside a step.
@@ -507,10 +507,10 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
         if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka, k_on);
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
-        // (grouped: looked up unconditionally, so that the table reads stay inside the straight-line
-        // block that follows instead of becoming a block of their own with its own waits)
-        if (kLists || kLeadThenLists || t + 2 < n_tiles) tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
-        if (kLists || kLeadThenLists || t + 1 < n_tiles) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
+        // (looked up unconditionally, also past the last tile, so that the table reads stay inside the
+        // straight-line block that follows instead of becoming a block of their own with its own waits)
+        tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
+        tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
 
     // tile 0: QK and weights only
