@@ -115,7 +115,8 @@ def main():
         kern_ms = [a.elapsed_time(b) for a, b in evs]
         fl, pairs = flops_of(count)
         return {"ms_per_step": wall_ms, "attn_kernel_ms_avg": float(np.mean(kern_ms)),
-                "attn_kernel_ms_min": float(np.min(kern_ms)), "flops": fl, "pairs": pairs}
+                "attn_kernel_ms_min": float(np.min(kern_ms)), "attn_kernel_ms_median": float(np.median(kern_ms)),
+                "flops": fl, "pairs": pairs}
 
     main_r = time_pattern(pattern, radius, args.steps, args.warmup)
     value = main_r["flops"] / (main_r["ms_per_step"] * 1e-3) / 1e12
@@ -213,7 +214,9 @@ def main():
                      # template arguments: waves per workgroup, mode (0 grouped, 2 joint), half?, head_dim
                      "kernel": "grat::attn_bf16_kernel<%d, %d, false, %d>" % (
                          8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
-                     "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4)},
+                     "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4),
+                     "kernel_ms_median": round(main_r["attn_kernel_ms_median"], 4),
+                     "kernel_ms_min": round(main_r["attn_kernel_ms_min"], 4)},
         "cpu_baseline": cpu,
         "dense": dense,
         "speedup_vs_dense": round(dense["kernel_ms"] / main_r["attn_kernel_ms_avg"], 2) if dense else None,
