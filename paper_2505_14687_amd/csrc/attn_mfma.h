@@ -535,11 +535,16 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
             if (t == mask_tile) mask_tail();
         }
         if (MODE == kRagged) mask_outside();
+        // From here on the step is a dependent chain of vector work with MFMAs of the previous tile
+        // in its gaps: the wave that is in it goes first, the SIMD's other wave fills in with its
+        // QK product (measured: +0.5 %; raising the QK part instead: -2 %).
+        __builtin_amdgcn_s_setprio(1);
         exp_half(0, pw_cur, ls);
         pv_half((t - 1) & 1, 0, pw_prev);
         exp_half(1, pw_cur, ls);
         pv_half((t - 1) & 1, 1, pw_prev);
         finish_softmax(pw_cur, ls);
+        __builtin_amdgcn_s_setprio(0);
     };
     auto walk = [&](auto check) {
         int t = 1;
