@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparison launch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-others", action="store_true", help="skip the workload's other patterns")
+    ap.add_argument("--no-probe", action="store_true", help="skip the MFMA-only probe")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--n-global", type=int, default=0,
                     help="prompt tokens ahead of the grid tokens (joint sequence, grat_attention_global_fwd)")
@@ -152,6 +153,24 @@ def main():
         dense = {"kernel_ms": round(d_ms, 3), "tflops": round(d_fl / (d_ms * 1e-3) / 1e12, 2)}
         log(f"dense: {dense}")
 
+    # what the MFMA instruction alone sustains on this machine (no memory traffic, no vector work)
+    probe = None
+    if not args.no_probe and w.dtype in ("bf16", "f16"):
+        blocks, iters, best = 256 * 16, 4096, None
+        sink = torch.empty(blocks * 256, dtype=torch.int64, device="cuda")
+        for i in range(4):   # the first launch is a warm-up
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            grat.grat_probe_mfma(Q.dtype, blocks, iters, sink=sink)
+            b.record()
+            torch.cuda.synchronize()
+            if i:
+                best = a.elapsed_time(b) if best is None else min(best, a.elapsed_time(b))
+        from paper_2505_14687_amd.grat import probe_wave_sum
+        assert bool(torch.all(sink.view(-1, 64).sum(1) == probe_wave_sum(iters))), "MFMA probe: wrong sums"
+        probe = blocks * 4.0 * iters * 8 * 32768 / (best * 1e-3) / 1e12
+        log(f"MFMA-only probe: {probe:.0f} TFLOP/s")
+
     cpu = None
     if not args.no_cpu:
         import psutil
@@ -214,6 +233,10 @@ def main():
                      # template arguments: waves per workgroup, mode (0 grouped, 2 joint), half?, head_dim
                      "kernel": "grat::attn_bf16_kernel<%d, %d, false, %d>" % (
                          8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
+                     # the same matrix instruction in a register-resident loop on this machine, and
+                     # `achieved` as a fraction of that
+                     "mfma_only_probe": round(probe, 1) if probe else None,
+                     "frac_of_probe": round(achieved / probe, 4) if probe else None,
                      "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4),
                      "kernel_ms_median": round(main_r["attn_kernel_ms_median"], 4),
                      "kernel_ms_min": round(main_r["attn_kernel_ms_min"], 4)},

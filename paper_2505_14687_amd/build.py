@@ -13,7 +13,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libgrat.so")
 # attn_mfma_*.hip: the instantiations of the MFMA kernel template (attn_mfma.h), one slice per
 # element type and head_dim, so that the slow part of the build runs side by side
-SOURCES = ["grat_api.hip", "block_lists.hip", "attn_f32.hip", "attn_mfma.hip",
+SOURCES = ["grat_api.hip", "block_lists.hip", "attn_f32.hip", "mfma_probe.hip", "attn_mfma.hip",
            "attn_mfma_bf16_d128.hip", "attn_mfma_bf16_d64.hip", "attn_mfma_f16_d128.hip", "attn_mfma_f16_d64.hip"]
 
 HIPCC_FLAGS = [

@@ -10,6 +10,7 @@ import ctypes
 import os
 from typing import Optional, Sequence, Tuple
 
+import numpy as np
 import torch
 
 from .build import LIB_PATH
@@ -19,7 +20,7 @@ PATTERNS = {"block": 0, "cross": 1, "cross_planes": 2, "dense": 3}
 DTYPES = {torch.bfloat16: 0, torch.float32: 1, torch.float16: 2}
 EXPORTS = ("grat_block_list_shape", "grat_build_block_lists", "grat_attention_fwd",
            "grat_attention_global_fwd", "grat_attention_packed_fwd", "grat_dense_attention_fwd",
-           "grat_status_string")
+           "grat_status_string", "grat_probe_mfma")
 
 _i32, _i64, _f32, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
 _pi32 = ctypes.POINTER(ctypes.c_int32)
@@ -60,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.grat_dense_attention_fwd.restype = _i32
         L.grat_status_string.argtypes = [_i32]
         L.grat_status_string.restype = ctypes.c_char_p
+        L.grat_probe_mfma.argtypes = [_i32, _vp, _i32, _i32, _vp]
+        L.grat_probe_mfma.restype = _i32
         _lib = L
     return _lib
 
@@ -187,3 +190,29 @@ def grat_dense_attention_fwd(Q, K, V, scale: float, out=None, stream=None):
     if st != GRAT_OK:
         raise GratError(st, "grat_dense_attention_fwd")
     return O
+
+
+def grat_probe_mfma(dtype, blocks: int, iters: int, sink=None, stream=None):
+    """One launch of the MFMA-only loop (grat_probe.h); returns the sink tensor [blocks * 256] int64."""
+    if sink is None:
+        sink = torch.empty(int(blocks) * 256, dtype=torch.int64, device="cuda")
+    if sink.dtype != torch.int64 or not sink.is_contiguous() or sink.numel() < int(blocks) * 256:
+        raise ValueError("sink: contiguous int64, at least blocks * 256 elements")
+    st = lib().grat_probe_mfma(DTYPES[dtype], sink.data_ptr(), int(blocks), int(iters), _stream_ptr(stream))
+    if st != GRAT_OK:
+        raise GratError(st, "grat_probe_mfma")
+    return sink
+
+
+def probe_wave_sum(iters: int) -> int:
+    """What the 64 sink values of one wave add up to (grat_probe.h): 8 * iters * sum_ij (A B)_ij."""
+    l = np.arange(64)[:, None]
+    e = np.arange(8)[None, :]
+    a = (37 * l + 11 * e + 5) % 9 - 4          # [lane, e] = A[i = l % 32][k = 8 (l // 32) + e]
+    b = (53 * l + 17 * e + 2) % 9 - 4
+    A = np.zeros((32, 16), dtype=np.int64)
+    B = np.zeros((16, 32), dtype=np.int64)
+    for lane in range(64):
+        A[lane % 32, 8 * (lane // 32):8 * (lane // 32) + 8] = a[lane]
+        B[8 * (lane // 32):8 * (lane // 32) + 8, lane % 32] = b[lane]
+    return int(8 * iters * (A @ B).sum())

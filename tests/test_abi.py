@@ -1,6 +1,7 @@
 """The C-ABI library loads, exports every symbol the header declares, and validates its
 arguments on the host (no launch happens on these paths, so no GPU is needed)."""
 import ctypes
+import glob
 import os
 import re
 
@@ -12,9 +13,11 @@ from paper_2505_14687_amd.build import LIB_PATH, ROOT
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "grat.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(grat_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(grat_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -131,3 +134,12 @@ def test_packed_entry_argument_errors():
     assert call(grid=(64, 60), n_global=8) == 3    # prompt tokens: whole groups only
     assert call(QKV=fake + 4) == 6                 # not 16-byte aligned
     assert call(max_kv=0) == 5
+
+
+def test_probe_argument_errors():
+    L = grat.lib()
+    fake = 0x1000
+    assert L.grat_probe_mfma(0, None, 256, 16, None) == 1
+    assert L.grat_probe_mfma(0, fake, 0, 16, None) == 2 and L.grat_probe_mfma(0, fake, 65537, 16, None) == 2
+    assert L.grat_probe_mfma(0, fake, 256, 0, None) == 2 and L.grat_probe_mfma(2, fake, 256, 4097, None) == 2
+    assert L.grat_probe_mfma(1, fake, 256, 16, None) == 6
