@@ -46,6 +46,10 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-others", action="store_true", help="skip the workload's other patterns")
     ap.add_argument("--no-probe", action="store_true", help="skip the MFMA-only probe")
+    ap.add_argument("--constant-data", action="store_true",
+                    help="context run, not the benchmark: Q = K = V = 1.0 everywhere (same launches, same "
+                         "traffic; shows how far the chip's clock under toggling data holds the kernel back); "
+                         "implies --no-cpu")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--n-global", type=int, default=0,
                     help="prompt tokens ahead of the grid tokens (joint sequence, grat_attention_global_fwd)")
@@ -75,6 +79,10 @@ def main():
             return torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
         return torch.from_numpy(x).cuda()
     Q, K, V = (dev(x) for x in host)
+    if args.constant_data:
+        args.no_cpu = True
+        for t in (Q, K, V):
+            t.fill_(1.0)
     O = torch.empty_like(Q)
     # one plain device copy of known size (Q -> O) ahead of everything: the reference against which
     # the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script are scaled
@@ -220,7 +228,7 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(main_r["ms_per_step"], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+        "dtype": w.dtype, "data": "constant 1.0 (context run)" if args.constant_data else "synthetic",
         "config": {"workload": f"{args.workload}: token grid {'x'.join(map(str, w.grid))}, groups "
                                f"{'x'.join(map(str, w.group))}, batch {w.batch}, {w.heads} heads, head_dim "
                                f"{w.head_dim}, {w.dtype}, pattern {args.pattern} ({pattern}, radius {list(radius)})"
