@@ -225,6 +225,8 @@ def main():
         cpu = {"value": cpu_flops / wall / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
                "sample": f"{done} seeded-random (head, query row) pairs of {args.workload} {args.pattern}, "
                          f"float64 numpy, {wall:.1f} s",
+               "seconds_per_row": wall / done,
+               "extrapolated_full_launch_s": main_r["flops"] / (cpu_flops / wall),
                "parity_max_abs": float(np.abs(diff).max()),
                "parity_rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(want))}
         log(f"cpu oracle: {cpu}")
