@@ -22,12 +22,16 @@ extern "C" {
  * four independent accumulators.  Work per launch: blocks * 4 * iters * 8 * 32 768 flop; the
  * caller times the launch (events on hip_stream).
  *
- * Operands: lane l (0..63) of a wave holds, as element e (0..7) of its A and B fragments, the
- * integers  A = (37 l + 11 e + 5) mod 9 - 4  and  B = (53 l + 17 e + 2) mod 9 - 4; in the
- * instruction's operand layout that is A[i][k] and B[k][j] with i = j = l mod 32 and
+ * Operands differ from lane to lane, element to element and instruction to instruction.  Of the
+ * eight instructions of an iteration, six work on full 8-bit significands (pseudo-random integers
+ * -128..127 over 16): accumulators 0..2 take A_v B_v and then A_v (-B_v), which returns them to
+ * exactly 0 (every partial sum is a multiple of 1/256 below 2^24).  Accumulator 3 takes two
+ * products of small integers per iteration: lane l (0..63) holds, as element e (0..7),
+ *   A = (37 l + 11 e + 5) mod 9 - 4,  B0 = (53 l + 17 e + 2) mod 9 - 4,  B1 = (57 l + 13 e + 7) mod 9 - 4,
+ * in the instruction's operand layout A[i][k] and B[k][j] with i = j = l mod 32 and
  * k = 8 (l div 32) + e.  Afterwards every lane adds up its 64 accumulator values (integers, exact)
  * into d_sink[block * 256 + thread]; the 64 sums of a wave therefore add up to
- * 8 * iters * sum_ij (A B)_ij — a check that the work was done.
+ * iters * sum_ij (A B0 + A B1)_ij — a check that the loop ran its count.
  *
  *   d_sink  DEVICE pointer, blocks * 256 int64, overwritten
  *   blocks  1 .. 65 536;  iters  1 .. 4096 (keeps every accumulator below 2^24)

@@ -205,14 +205,17 @@ def grat_probe_mfma(dtype, blocks: int, iters: int, sink=None, stream=None):
 
 
 def probe_wave_sum(iters: int) -> int:
-    """What the 64 sink values of one wave add up to (grat_probe.h): 8 * iters * sum_ij (A B)_ij."""
+    """What the 64 sink values of one wave add up to (grat_probe.h)."""
     l = np.arange(64)[:, None]
     e = np.arange(8)[None, :]
-    a = (37 * l + 11 * e + 5) % 9 - 4          # [lane, e] = A[i = l % 32][k = 8 (l // 32) + e]
-    b = (53 * l + 17 * e + 2) % 9 - 4
-    A = np.zeros((32, 16), dtype=np.int64)
-    B = np.zeros((16, 32), dtype=np.int64)
-    for lane in range(64):
-        A[lane % 32, 8 * (lane // 32):8 * (lane // 32) + 8] = a[lane]
-        B[8 * (lane // 32):8 * (lane // 32) + 8, lane % 32] = b[lane]
-    return int(8 * iters * (A @ B).sum())
+
+    def matrix(values):   # [lane, e] -> M[l % 32][8 (l // 32) + e]
+        M = np.zeros((32, 16), dtype=np.int64)
+        for lane in range(64):
+            M[lane % 32, 8 * (lane // 32):8 * (lane // 32) + 8] = values[lane]
+        return M
+
+    A = matrix((37 * l + 11 * e + 5) % 9 - 4)
+    B0 = matrix((53 * l + 17 * e + 2) % 9 - 4).T
+    B1 = matrix((57 * l + 13 * e + 7) % 9 - 4).T
+    return int(iters * ((A @ B0).sum() + (A @ B1).sum()))
