@@ -162,25 +162,29 @@ def main():
         log(f"dense: {dense}")
 
     # what the MFMA instruction alone sustains on this machine (no memory traffic, no vector work)
-    probe = None
+    probe = probe_ones = None
     if not args.no_probe and w.dtype in ("bf16", "f16"):
         try:   # (an aid: a failure here must not cost the benchmark line)
             from paper_2505_14687_amd.grat import probe_wave_sum
-            blocks, iters, best = 256 * 16, 4096, None
+            blocks, iters = 256 * 16, 4096
             sink = torch.empty(blocks * 256, dtype=torch.int64, device="cuda")
-            for i in range(4):   # the first launch is a warm-up
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                grat.grat_probe_mfma(Q.dtype, blocks, iters, sink=sink)
-                b.record()
-                torch.cuda.synchronize()
-                if i:
-                    best = a.elapsed_time(b) if best is None else min(best, a.elapsed_time(b))
-            if bool(torch.all(sink.view(-1, 64).sum(1) == probe_wave_sum(iters))):
-                probe = blocks * 4.0 * iters * 8 * 32768 / (best * 1e-3) / 1e12
-                log(f"MFMA-only probe: {probe:.0f} TFLOP/s")
-            else:
-                log("MFMA-only probe: wrong sums, not reported")
+            rates = {}
+            for kind in ("normal_like", "ones"):
+                best = None
+                for i in range(4):   # the first launch is a warm-up
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    grat.grat_probe_mfma(Q.dtype, kind, blocks, iters, sink=sink)
+                    b.record()
+                    torch.cuda.synchronize()
+                    if i:
+                        best = a.elapsed_time(b) if best is None else min(best, a.elapsed_time(b))
+                if bool(torch.all(sink.view(-1, 64).sum(1) == probe_wave_sum(kind, iters))):
+                    rates[kind] = blocks * 4.0 * iters * 8 * 32768 / (best * 1e-3) / 1e12
+                else:
+                    log(f"MFMA-only probe ({kind}): wrong sums, not reported")
+            probe, probe_ones = rates.get("normal_like"), rates.get("ones")
+            log(f"MFMA-only probe: {rates}")
             del sink
         except Exception as e:   # noqa: BLE001
             log(f"MFMA-only probe failed: {e!r}")
@@ -249,9 +253,11 @@ def main():
                      # template arguments: waves per workgroup, mode (0 grouped, 2 joint), half?, head_dim
                      "kernel": "grat::attn_bf16_kernel<%d, %d, false, %d>" % (
                          8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
-                     # the same matrix instruction in a register-resident loop on this machine, and
-                     # `achieved` as a fraction of that
+                     # the same matrix instruction in a register-resident loop on this machine (operands
+                     # with full significands spread like N(0,1); then all ones), and `achieved` as a
+                     # fraction of the former
                      "mfma_only_probe": round(probe, 1) if probe else None,
+                     "mfma_only_probe_constant_operands": round(probe_ones, 1) if probe_ones else None,
                      "frac_of_probe": round(achieved / probe, 4) if probe else None,
                      "kernel_ms_avg": round(main_r["attn_kernel_ms_avg"], 4),
                      "kernel_ms_median": round(main_r["attn_kernel_ms_median"], 4),

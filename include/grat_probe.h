@@ -22,26 +22,32 @@ extern "C" {
  * four independent accumulators.  Work per launch: blocks * 4 * iters * 8 * 32 768 flop; the
  * caller times the launch (events on hip_stream).
  *
- * Operands differ from lane to lane, element to element and instruction to instruction.  Of the
- * eight instructions of an iteration, six work on full 8-bit significands (pseudo-random integers
- * -128..127 over 16): accumulators 0..2 take A_v B_v and then A_v (-B_v), which returns them to
- * exactly 0 (every partial sum is a multiple of 1/256 below 2^24).  Accumulator 3 takes two
- * products of small integers per iteration: lane l (0..63) holds, as element e (0..7),
- *   A = (37 l + 11 e + 5) mod 9 - 4,  B0 = (53 l + 17 e + 2) mod 9 - 4,  B1 = (57 l + 13 e + 7) mod 9 - 4,
- * in the instruction's operand layout A[i][k] and B[k][j] with i = j = l mod 32 and
- * k = 8 (l div 32) + e.  Afterwards every lane adds up its 64 accumulator values (integers, exact)
- * into d_sink[block * 256 + thread]; the 64 sums of a wave therefore add up to
- * iters * sum_ij (A B0 + A B1)_ij — a check that the loop ran its count.
+ * What the instruction sustains depends on how its operands toggle, so `data` chooses them.  In
+ * every iteration accumulator v (0..3) takes A_v B_v and then A_v B'_v:
+ *   data 0  all operands 1.0, B' = B;
+ *   data 1  small integers, B' = B: lane l (0..63) holds, as element e (0..7),
+ *             A_v = ((37 + 2v) l + 11 e + 5 + 3v) mod 9 - 4,  B_v = ((53 + 2v) l + 17 e + 2 + 3v) mod 9 - 4,
+ *           in the instruction's operand layout A[i][k] and B[k][j] with i = j = l mod 32 and
+ *           k = 8 (l div 32) + e;
+ *   data 2  the stand-in for real activations: for v < 3 pseudo-random n / 64 with n an integer of at
+ *           most 8 significant bits spread roughly like 64 N(0,1), and B' = -B, which returns these
+ *           accumulators to exactly 0 (every partial sum is a multiple of 1/4096 below 2^24);
+ *           v = 3 as under data 1.
+ * Afterwards every lane adds up its 64 accumulator values (integers, exact) into
+ * d_sink[block * 256 + thread]; the 64 sums of a wave add up to iters * 2 * sum_ij (A_v B_v)_ij
+ * summed over the accumulators that count (data 0, 1: all four; data 2: v = 3) — a check that the
+ * loop ran its count.
  *
+ *   data    0 .. 2
  *   d_sink  DEVICE pointer, blocks * 256 int64, overwritten
  *   blocks  1 .. 65 536;  iters  1 .. 4096 (keeps every accumulator below 2^24)
  *
- * Errors: GRAT_ERR_NULL (d_sink), GRAT_ERR_BAD_DIMS (blocks, iters out of range),
+ * Errors: GRAT_ERR_NULL (d_sink), GRAT_ERR_BAD_DIMS (data, blocks, iters out of range),
  * GRAT_ERR_UNSUPPORTED (dtype GRAT_F32: no matrix path), GRAT_ERR_HIP; nothing is launched on an
  * error other than GRAT_ERR_HIP.  Allocates nothing, does not synchronise.
  */
-grat_status grat_probe_mfma(grat_dtype dtype, int64_t* d_sink, int32_t blocks, int32_t iters,
-                            void* hip_stream);
+grat_status grat_probe_mfma(grat_dtype dtype, int32_t data, int64_t* d_sink, int32_t blocks,
+                            int32_t iters, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -139,7 +139,8 @@ def test_packed_entry_argument_errors():
 def test_probe_argument_errors():
     L = grat.lib()
     fake = 0x1000
-    assert L.grat_probe_mfma(0, None, 256, 16, None) == 1
-    assert L.grat_probe_mfma(0, fake, 0, 16, None) == 2 and L.grat_probe_mfma(0, fake, 65537, 16, None) == 2
-    assert L.grat_probe_mfma(0, fake, 256, 0, None) == 2 and L.grat_probe_mfma(2, fake, 256, 4097, None) == 2
-    assert L.grat_probe_mfma(1, fake, 256, 16, None) == 6
+    assert L.grat_probe_mfma(0, 2, None, 256, 16, None) == 1
+    assert L.grat_probe_mfma(0, 2, fake, 0, 16, None) == 2 and L.grat_probe_mfma(0, 2, fake, 65537, 16, None) == 2
+    assert L.grat_probe_mfma(0, 2, fake, 256, 0, None) == 2 and L.grat_probe_mfma(2, 2, fake, 256, 4097, None) == 2
+    assert L.grat_probe_mfma(0, 3, fake, 256, 16, None) == 2 and L.grat_probe_mfma(0, -1, fake, 256, 16, None) == 2
+    assert L.grat_probe_mfma(1, 0, fake, 256, 16, None) == 6
