@@ -165,7 +165,7 @@ def main():
     probe = probe_ones = None
     if not args.no_probe and w.dtype in ("bf16", "f16"):
         try:   # (an aid: a failure here must not cost the benchmark line)
-            from paper_2505_14687_amd.grat import probe_wave_sum
+            from paper_2505_14687_amd.probe import probe_wave_sum
             blocks, iters = 256 * 16, 4096
             sink = torch.empty(blocks * 256, dtype=torch.int64, device="cuda")
             rates = {}

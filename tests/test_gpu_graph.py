@@ -88,7 +88,7 @@ def test_side_stream_is_the_launch_stream():
 @pytest.mark.parametrize("data", ["ones", "small_ints", "normal_like"])
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
 def test_mfma_probe_does_its_work(dtype, data):
-    from paper_2505_14687_amd.grat import probe_wave_sum
+    from paper_2505_14687_amd.probe import probe_wave_sum
     sink = grat.grat_probe_mfma(dtype, data, 512, 64)
     torch.cuda.synchronize()
     assert sink.shape == (512 * 256,)
