@@ -156,13 +156,15 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
 
     const Geometry& geo = p.geo;
     const int tiles_per_head = dense ? p.q_tiles_dense : geo.num_groups * p.q_tiles;
-    const int bh = tile / tiles_per_head;
-    const int t_in_head = tile % tiles_per_head;
-    const int64_t head_off = (int64_t)(bh / p.heads) * p.stride_b + (int64_t)(bh % p.heads) * p.stride_h;
+    // (index decompositions go through host-prepared multipliers: see fastdiv.h)
+    const int bh = (int)fdiv((uint32_t)tile, dense ? p.fd_tiles_per_head_dense : p.fd_tiles_per_head);
+    const int t_in_head = tile - bh * tiles_per_head;
+    const int b_idx = (int)fdiv((uint32_t)bh, p.fd_heads), h_idx = bh - b_idx * p.heads;
+    const int64_t head_off = (int64_t)b_idx * p.stride_b + (int64_t)h_idx * p.stride_h;
     const uint16_t* Qh = (const uint16_t*)p.Q + head_off;
     const uint16_t* Kh = (const uint16_t*)p.K + head_off;
     const uint16_t* Vh = (const uint16_t*)p.V + head_off;
-    uint16_t* Oh = (uint16_t*)p.O + (int64_t)(bh / p.heads) * p.o_stride_b + (int64_t)(bh % p.heads) * p.o_stride_h;
+    uint16_t* Oh = (uint16_t*)p.O + (int64_t)b_idx * p.o_stride_b + (int64_t)h_idx * p.o_stride_h;
     const int stride_n = p.stride_n;
 
     // s_rowbytes[t]: byte offset (row * stride_n * 2) of intra-group token t relative to its group's
@@ -194,13 +196,30 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
         if (p.n_tokens % kBN) { mask_tile = n_tiles - 1; mask_valid = p.n_tokens % kBN; }
         q_first = t_in_head * BM + wave * 32;
     } else {
-        const int gamma = strip_order_group(t_in_head / p.q_tiles, geo.G[0] * geo.G[1], geo.G[2], p.strip_w);
-        const int qt = t_in_head % p.q_tiles;
+        const uint32_t u_group = fdiv((uint32_t)t_in_head, p.fd_q_tiles);
+        const int qt = t_in_head - (int)u_group * p.q_tiles;
+        const int gamma = strip_order_group_fast(u_group, geo.G[0] * geo.G[1], geo.G[2], p);
         const int n_g = geo.group_tokens;
-        const int T12 = geo.T[1] * geo.T[2], g12 = geo.g[1] * geo.g[2], G12 = geo.G[1] * geo.G[2];
+        const int T12 = geo.T[1] * geo.T[2];
+        // row of the first token of group gid, relative to the first grid row
+        auto group_origin = [&](uint32_t gid, int& p0, int& p1, int& p2) {
+            uint32_t v, r2, q0, r1;
+            fdivmod(gid, p.fd_G2, v, r2);
+            fdivmod(v, p.fd_G1, q0, r1);
+            p0 = (int)q0; p1 = (int)r1; p2 = (int)r2;
+            return p0 * geo.g[0] * T12 + p1 * geo.g[1] * geo.T[2] + p2 * geo.g[2];
+        };
+        // box coordinates of token t of a group
+        auto token_coord = [&](uint32_t t, int& c0, int& c1, int& c2) {
+            uint32_t v, r2, q0, r1;
+            fdivmod(t, p.fd_g2, v, r2);
+            fdivmod(v, p.fd_g1, q0, r1);
+            c0 = (int)q0; c1 = (int)r1; c2 = (int)r2;
+        };
         const uint32_t grid_base = MODE == kJoint ? (uint32_t)p.grid_row0 : 0u;   // first grid row
         auto box_limit = [&](int gid) {   // largest box coordinates of group gid inside the grid
-            const int p0 = gid / G12, p1 = (gid / geo.G[2]) % geo.G[1], p2 = gid % geo.G[2];
+            int p0, p1, p2;
+            group_origin((uint32_t)gid, p0, p1, p2);
             return pack_coord(min(geo.g[0], geo.T[0] - p0 * geo.g[0]) - 1, min(geo.g[1], geo.T[1] - p1 * geo.g[1]) - 1,
                               min(geo.g[2], geo.T[2] - p2 * geo.g[2]) - 1);
         };
@@ -208,12 +227,12 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
         // rather than read from the table below: they come from HBM (nobody has touched them
         // before) and everything up to the first barrier then happens in the shadow of that fetch.
         {
-            const int q_origin = (gamma / G12) * geo.g[0] * T12 + ((gamma / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
-                                 (gamma % geo.G[2]) * geo.g[2];
+            int gp0, gp1, gp2;
+            const int q_origin = group_origin((uint32_t)gamma, gp0, gp1, gp2);
             q_base = grid_base + (uint32_t)q_origin;
             q_first = qt * BM + wave * 32;
-            const int t = q_first + qcol;
-            const int c0 = t / g12, c1 = (t / geo.g[2]) % geo.g[1], c2 = t % geo.g[2];
+            int c0, c1, c2;
+            token_coord((uint32_t)(q_first + qcol), c0, c1, c2);
             uint32_t off = (uint32_t)(c0 * T12 + c1 * geo.T[2] + c2) * row_pitch;
             if (MODE == kRagged) {
                 q_limit = box_limit(gamma);
@@ -224,16 +243,16 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
             for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = ks < D / 16 ? *(const frag8*)(src + 32 * ks) : frag8{0, 0, 0, 0, 0, 0, 0, 0};
         }
         for (int t = tid; t < n_g; t += NT) {
-            const int c0 = t / g12, c1 = (t / geo.g[2]) % geo.g[1], c2 = t % geo.g[2];
+            int c0, c1, c2;
+            token_coord((uint32_t)t, c0, c1, c2);
             s_rowbytes[t] = (uint32_t)(c0 * T12 + c1 * geo.T[2] + c2) * row_pitch;
             if (MODE == kRagged) s_coord[t] = pack_coord(c0, c1, c2);
         }
         const int cnt = p.kv_count[gamma];
         for (int i = tid; i < cnt; i += NT) {
             const int gid = p.kv_index[(int64_t)gamma * p.max_kv + i];
-            s_origin[i] = grid_base +
-                          (uint32_t)((gid / G12) * geo.g[0] * T12 + ((gid / geo.G[2]) % geo.G[1]) * geo.g[1] * geo.T[2] +
-                                     (gid % geo.G[2]) * geo.g[2]);
+            int p0, p1, p2;
+            s_origin[i] = grid_base + (uint32_t)group_origin((uint32_t)gid, p0, p1, p2);
             if (MODE == kRagged) s_limit[i] = box_limit(gid);
         }
         __syncthreads();

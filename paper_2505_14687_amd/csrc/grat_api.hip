@@ -147,6 +147,24 @@ extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid,
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }
 
+// Divisors of the MFMA kernel's index decompositions, from the finished launch parameters.
+static void fill_fastdivs(AttnParams& p) {
+    const Geometry& geo = p.geo;
+    p.fd_tiles_per_head = make_fastdiv((uint32_t)geo.num_groups * (uint32_t)p.q_tiles);
+    p.fd_tiles_per_head_dense = make_fastdiv((uint32_t)p.q_tiles_dense);
+    p.fd_heads = make_fastdiv((uint32_t)p.heads);
+    p.fd_q_tiles = make_fastdiv((uint32_t)p.q_tiles);
+    const int rows = geo.G[0] * geo.G[1], cols = geo.G[2], sw = p.strip_w > 0 ? p.strip_w : 1;
+    p.strip_full = cols / sw;
+    p.fd_strip = make_fastdiv((uint32_t)rows * (uint32_t)sw);
+    p.fd_strip_w = make_fastdiv((uint32_t)sw);
+    p.fd_strip_tail = make_fastdiv((uint32_t)(cols - p.strip_full * sw));   // (0 becomes 1: no tail strip, never used)
+    p.fd_g1 = make_fastdiv((uint32_t)geo.g[1]);
+    p.fd_g2 = make_fastdiv((uint32_t)geo.g[2]);
+    p.fd_G1 = make_fastdiv((uint32_t)geo.G[1]);
+    p.fd_G2 = make_fastdiv((uint32_t)geo.G[2]);
+}
+
 struct OutStrides { int64_t b, h, n; };   // O's own strides (elements)
 
 // LDS the MFMA kernel needs beside its four 16-KiB tiles: the row-offset table of a group and the
@@ -226,6 +244,7 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
         p.q_tiles_dense = (n_global + bm - 1) / bm;
         p.n_dense_tiles = batch * heads * p.q_tiles_dense;
     }
+    fill_fastdivs(p);
     const hipError_t e = is16(dtype)
                              ? launch_attn_bf16(p, mode, dtype == GRAT_F16, head_dim, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, false, (hipStream_t)hip_stream);
@@ -306,6 +325,7 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
+    fill_fastdivs(p);
     const hipError_t e = is16(dtype)
                              ? launch_attn_bf16(p, kDense, dtype == GRAT_F16, head_dim, (hipStream_t)hip_stream)
                              : launch_attn_f32(p, head_dim, true, (hipStream_t)hip_stream);

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fastdiv.h"
 #include "grat.h"
 
 namespace grat {
@@ -45,6 +46,13 @@ struct AttnParams {
     int32_t n_global;          // prompt tokens
     int32_t global_row0;       // first prompt row
     int32_t grid_row0;         // first grid row
+    // MFMA kernel: host-prepared divisors for the index decompositions of its prologue
+    FastDiv fd_tiles_per_head;        // by num_groups * q_tiles (grouped tiles)
+    FastDiv fd_tiles_per_head_dense;  // by q_tiles_dense
+    FastDiv fd_heads, fd_q_tiles;
+    FastDiv fd_strip, fd_strip_w, fd_strip_tail;   // strip order: by rows * strip_w, strip_w, width of the last strip
+    int32_t strip_full;               // full strips: cols / strip_w
+    FastDiv fd_g1, fd_g2, fd_G1, fd_G2;            // token in group -> box coordinates, group id -> group coordinates
 };
 
 // What a workgroup of the MFMA attention kernel can be (its MODE template argument).
@@ -80,6 +88,15 @@ inline int xcd_padded_blocks(int total) { return ((total + kNumXcd - 1) / kNumXc
 // runs at a time then cover a compact 2D patch of groups (4 rows x 8 columns for strip_w = 8)
 // whose K/V neighbourhoods overlap in both directions, instead of one long group-row.
 // rows = all leading group axes flattened, cols = the last group axis; returns the linear group id.
+__device__ __forceinline__ int strip_order_group_fast(uint32_t u, int rows, int cols, const AttnParams& p) {
+    uint32_t s = fdiv(u, p.fd_strip);
+    int w = p.strip_w;
+    FastDiv fw = p.fd_strip_w;
+    if ((int)s >= p.strip_full) { s = p.strip_full; w = cols - p.strip_full * p.strip_w; fw = p.fd_strip_tail; }
+    const uint32_t v = u - s * (uint32_t)(rows * p.strip_w);
+    const uint32_t vq = fdiv(v, fw);
+    return (int)(vq * cols + s * p.strip_w + (v - vq * w));
+}
 __device__ __forceinline__ int strip_order_group(int u, int rows, int cols, int strip_w) {
     const int full = cols / strip_w;
     int s = u / (rows * strip_w), w = strip_w;
