@@ -316,8 +316,19 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
         uint32_t base;        // wave-uniform
         uint32_t off[LPW];    // per lane
     };
-    int gi_k = 0, j_k = 0, gi_v = 0, j_v = 0;   // list entry / tile-in-group of the next K and V tile
+    int gi_k = 0, j_k = 0, gi_v = 0, j_v = 0;   // list entry / tile-in-group of the next K (dense walk: and V) tile
     TileAddr ka, va;
+    // V(t) lies in the rows of K(t): where the rows come out of table reads, its address is taken
+    // from K's with the other swizzle in the column part instead of being looked up again (+0.7 %;
+    // the dense walk, whose addresses are arithmetic, measured 1 % slower that way and forms both)
+    uint32_t k_to_vcol[LPW];
+#pragma unroll
+    for (int k = 0; k < LPW; ++k) k_to_vcol[k] = load_vcol[k] - load_kcol[k];
+    auto v_from_k = [&](TileAddr& v, const TileAddr& kk) {
+        v.base = kk.base;
+#pragma unroll
+        for (int k = 0; k < LPW; ++k) v.off[k] = kk.off[k] + k_to_vcol[k];
+    };
     // Offsets of a tile are looked up one tile before it is fetched, so the table reads never sit
     // between a barrier and the loads that follow it.
     auto tile_addr = [&](TileAddr& a, const uint32_t* col, int t, int& gi, int& j) {
@@ -516,8 +527,9 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
     // ---- prologue: K tile 0 -----------------------------------------------------------------
     tile_addr(ka, load_kcol, 0, gi_k, j_k);
     issue_tile(Kh, sK[0], ka, k_on);
+    if (dense) tile_addr(va, load_vcol, 0, gi_v, j_v);
+    else v_from_k(va, ka);
     if (1 < n_tiles) tile_addr(ka, load_kcol, 1, gi_k, j_k);
-    tile_addr(va, load_vcol, 0, gi_v, j_v);
 
     // swap_barrier(t) publishes K(t) and V(t-1), fetched during the previous tile, and frees the
     // buffers of K(t-1) and V(t-2), which are refilled with K(t+1) and V(t) right away.
@@ -528,8 +540,9 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
         // (looked up unconditionally, also past the last tile, so that the table reads stay inside the
         // straight-line block that follows instead of becoming a block of their own with its own waits)
+        if (dense) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
+        else v_from_k(va, ka);   // tile t + 1, whose K part has just been asked for
         tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
-        tile_addr(va, load_vcol, t + 1, gi_v, j_v);
     };
 
     // tile 0: QK and weights only
