@@ -23,13 +23,16 @@
 //          LDS transpose read ds_read_b64_tr_b16.
 // Softmax runs in base 2 with scale*log2(e) folded into one FMA per score; the reference
 // maximum, the running sum and the O accumulator stay fp32; P is rounded to bf16 (RNE) for the
-// second product and the row sum is taken over those rounded weights.
+// second product; the row sum is taken over the unrounded fp32 weights with plain adds.
 //
-// Schedule: one barrier per KV tile.  Within a tile every wave runs, as ONE straight-line
-// block, the QK product of tile t and the weights of tile t next to the PV product of tile t-1
-// (P is double buffered, PV lags QK by a tile), so each stretch of vector-ALU work has
-// independent MFMAs of the same wave to hide behind, and the two waves of a SIMD fill each
-// other's remaining gaps.
+// Schedule: one barrier per KV tile, and between two barriers ONE instruction stream per wave in
+// which the work is software-pipelined by 32-key blocks (half a tile): while the matrix pipe forms
+// the scores of block h, the vector ALU turns the scores of block h-1 into weights and the matrix
+// pipe adds block h-2 to O.  The three stages of a half step do not depend on each other, so every
+// MFMA is followed by its share of the vector work: a 32x32x16 MFMA holds the matrix pipe for 32
+// cycles but the issue port for 8, and 24 cycles of other vector instructions fit behind it.
+// (Measured on this chip: v_dot2c_f32_bf16 is not among them - it waits for the matrix pipe and
+// holds it for 16 cycles - which is why the row sum uses v_add_f32.)
 #pragma once
 #include <type_traits>
 
@@ -52,6 +55,7 @@ constexpr int kD = 128;               // head_dim
 constexpr int kBN = 64;               // KV tokens per LDS tile
 constexpr int kRowBytes = kD * 2;     // 256 B per token row
 constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB
+constexpr int kFragAhead = 2;         // an MFMA's LDS fragment is read this many MFMAs ahead of it
 
 // LDS tiles are unpadded [64 rows][16 chunks of 16 B]; the chunk index is XOR-swizzled per row so
 // that the fragment reads are bank-conflict free.  K is read with ds_read_b128 by lanes holding
@@ -65,7 +69,7 @@ __device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 2; }
 // travel as type-neutral frag8 and are reinterpreted at the MFMA.
 template <bool F16>
 struct Elem {
-    // a lane's tile row sum (32 weights) beyond this forces a new reference maximum: every single
+    // a lane's block row sum (16 weights) beyond this forces a new reference maximum: every single
     // weight then stays inside the type's range (half: 65504) with its full relative precision
     static constexpr float kSumLimit = F16 ? 0x1p+15f : 0x1p+40f;
     static __device__ __forceinline__ f32x16 mfma(frag8 a, frag8 b, f32x16 c) {
@@ -79,16 +83,6 @@ struct Elem {
         const f32x2 v = {lo, hi};
         if constexpr (F16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
         else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-    }
-    // acc + both halves of a packed pair (one packed dot product with (1, 1))
-    static __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
-        if constexpr (F16) {
-            const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-            return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), ones, acc, false);
-        } else {
-            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-            return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, acc, false);
-        }
     }
 };
 
@@ -131,12 +125,12 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
 // the 4 fragments that exist, and the upper half of O^T is never formed, so no MFMA or LDS read is
 // spent on padding (the unused chunk positions are never written and never read).
 //
-// One query tile.  `tile` = its index among the tiles of its kind; DENSE: it is a tile of consecutive
+// One query tile: tile t_in_head of its kind in (batch, head) bh.  DENSE: it is a tile of consecutive
 // query rows that walks the whole sequence (always in kDense, the prompt rows in kJoint), else a
 // tile of one query group.  sK / sV: the workgroup's two K and two V tile buffers in LDS.
 template <int NWAVES, int MODE, bool F16, int D, bool DENSE>
-__device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, uint8_t (*sK)[kTileBytes],
-                                          uint8_t (*sV)[kTileBytes]) {
+__device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, const int t_in_head,
+                                          uint8_t (*sK)[kTileBytes], uint8_t (*sV)[kTileBytes]) {
     static_assert(D == 128 || D == 64, "head_dim 128 or 64");
     using E = Elem<F16>;
     constexpr int NT = NWAVES * 64;
@@ -155,10 +149,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
     const int half = lane >> 5;
 
     const Geometry& geo = p.geo;
-    const int tiles_per_head = dense ? p.q_tiles_dense : geo.num_groups * p.q_tiles;
     // (index decompositions go through host-prepared multipliers: see fastdiv.h)
-    const int bh = (int)fdiv((uint32_t)tile, dense ? p.fd_tiles_per_head_dense : p.fd_tiles_per_head);
-    const int t_in_head = tile - bh * tiles_per_head;
     const int b_idx = (int)fdiv((uint32_t)bh, p.fd_heads), h_idx = bh - b_idx * p.heads;
     const int64_t head_off = (int64_t)b_idx * p.stride_b + (int64_t)h_idx * p.stride_h;
     const uint16_t* Qh = (const uint16_t*)p.Q + head_off;
@@ -278,11 +269,11 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
         for (int ks = 0; ks < kD / 16; ++ks) qf[ks] = ks < D / 16 ? *(const frag8*)(src + 32 * ks) : frag8{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
-    f32x16 oacc[kD / 32];                 // O^T accumulator: 4 blocks of 32 head dims
-    f32x16 S[2];                          // S^T of the current tile: 2 blocks of 32 keys
-    uint32_t pwA[2][8], pwB[2][8];        // P^T of two consecutive tiles as bf16 pairs, in accumulator order
+    f32x16 oacc[D / 32];                  // O^T accumulator: blocks of 32 head dims
+    f32x16 S[2];                          // S^T of the two 32-key blocks in flight
+    uint32_t pw[2][8];                    // their weights P^T as 16-bit pairs, in accumulator order
 #pragma unroll
-    for (int db = 0; db < kD / 32; ++db)
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
 #pragma unroll
@@ -290,10 +281,10 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
 #pragma unroll
         for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) { pwA[kb][r] = 0u; pwB[kb][r] = 0u; }
+        for (int r = 0; r < 8; ++r) pw[kb][r] = 0u;
     }
     float m_ref = -INFINITY;   // reference maximum of raw scores the weights are taken against
-    float l_run = 0.f;         // this lane's share of the running sum (its 32 keys per tile)
+    float l_run = 0.f;         // this lane's share of the running sum (its 16 keys per block)
     const float c = p.scale_log2;
 
     // ---- tile loads: LPW one-KiB pieces per wave; lane -> (row = 4*piece + lane/16, chunk) ----
@@ -393,135 +384,89 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
     // chunk = 4*db + 2*dsel + cq/2, swizzled with 4*(row & 3) = 4*e  ->  4*(db ^ e) + 2*dsel + cq/2
     const int v_chunk_lo = 2 * tr_dsel + (tr_cq >> 1);
 
-    // QK for the 32-key block kb of the tile in sK[kbuf]: D/16 fragment reads and MFMAs
-    auto qk_half = [&](int kbuf, int kb) {
-        const uint8_t* kt = sK[kbuf] + k_lane_base + kb * 32 * kRowBytes;
+    // ---- the software pipeline ---------------------------------------------------------------
+    // Work is cut into 32-key blocks (half a K/V tile).  For block h the three stages run one half
+    // step apart:  QK(h) -> S[h % 2]   |   weights(h-1): S[(h-1) % 2] -> pw[(h-1) % 2]   |
+    // PV(h-2) with pw[h % 2].  Inside a half step the three streams are independent of each other,
+    // so the vector work can be dealt out evenly between the MFMAs: a 32x32x16 MFMA occupies the
+    // matrix pipe for 32 cycles but the issue port for only 8, and up to 24 cycles of other vector
+    // instructions fit in its shadow.  (The packed dot product is not one of them: it runs on the
+    // matrix pipe and waits for it, so the row sum is taken with plain adds.)
+    // (the per-lane part of the K fragment addresses is formed once and pinned in registers: left to
+    // itself the compiler re-adds the swizzled chunk offset in front of every read)
+    uint32_t k_addr[D / 16];
 #pragma unroll
-        for (int j = 0; j < D / 64; ++j) {   // 16 head dims per fragment, 4 fragments at a time
-            frag8 f[4];
+    for (int ks = 0; ks < D / 16; ++ks) {
+        k_addr[ks] = (uint32_t)(uintptr_t)(LDS_PTR(uint8_t))(&sK[0][0] + k_lane_base + (((2 * ks) ^ k_x) << 4));
+        asm volatile("" : "+v"(k_addr[ks]));
+    }
+    auto k_frag = [&](int kbuf, int kb, int ks) -> frag8 {
+        return *(LDS_PTR(const frag8))(uintptr_t)(k_addr[ks] + kbuf * kTileBytes + kb * 32 * kRowBytes);
+    };
+    auto v_frag = [&](int vbuf, int kb, int s2, int db) -> frag8 {
+        const uint8_t* src = sV[vbuf] + v_lane_base + (32 * kb + 16 * s2) * kRowBytes + ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))src);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(src + 8 * kRowBytes));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    auto mask_tail = [&](int kb) {   // the ragged tile: keys past the end of their run get weight 0
 #pragma unroll
-            for (int i = 0; i < 4; ++i) f[i] = *(const frag8*)(kt + (((2 * (4 * j + i)) ^ k_x) << 4));
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int ks = 4 * j + i;
-                if (ks == 0) {
-                    f32x16 zero;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-                    S[kb] = E::mfma(f[i], qf[ks], zero);
-                } else {
-                    S[kb] = E::mfma(f[i], qf[ks], S[kb]);
-                }
-            }
+        for (int r = 0; r < 16; ++r) {
+            const int key = 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (key >= mask_valid) S[kb][r] = -INFINITY;
         }
     };
-    // PV for the two 16-key steps of key block kb of the tile in sV[vbuf]: 16 transpose reads, 8 MFMAs
-    auto pv_half = [&](int vbuf, int kb, const uint32_t (&pw)[2][8]) {
-        const uint8_t* vt = sV[vbuf] + v_lane_base;
+    // kRagged: called once per 32-key block, in walk order.  Keys of a border group's box that lie
+    // outside the grid get weight 0.  (The first block of every box holds its first token, which is
+    // always inside, so the first block of a walk never ends up without a finite score.)
+    int gi_m = 0, j_m = 0;   // list entry / tile-in-group of the tile whose scores are being weighted
+    const uint32_t full_box = pack_coord(geo.g[0] - 1, geo.g[1] - 1, geo.g[2] - 1);
+    auto mask_outside = [&](int kb) {
+        const uint32_t lim = __builtin_amdgcn_readfirstlane(s_limit[min(gi_m, n_listed - 1)]);
+        if (lim != full_box) {
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            frag8 f[4];
-#pragma unroll
-            for (int db = 0; db < kD / 32; ++db) {
-                const int col = ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
-                const uint8_t* src = vt + (32 * kb + 16 * s2) * kRowBytes + col;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))src);
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(src + 8 * kRowBytes));
-                f[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            for (int rq = 0; rq < 4; ++rq) {
+                // accumulator registers 4*rq .. 4*rq+3 hold 4 consecutive keys
+                const uint4 cc = *(const uint4*)&s_coord[j_m * kBN + 32 * kb + 8 * rq + 4 * half];
+                if (!coord_inside(cc.x, lim)) S[kb][4 * rq] = -INFINITY;
+                if (!coord_inside(cc.y, lim)) S[kb][4 * rq + 1] = -INFINITY;
+                if (!coord_inside(cc.z, lim)) S[kb][4 * rq + 2] = -INFINITY;
+                if (!coord_inside(cc.w, lim)) S[kb][4 * rq + 3] = -INFINITY;
             }
-            const uint32_t* w = &pw[kb][4 * s2];
-            const frag8 b = __builtin_bit_cast(frag8, make_uint4(w[0], w[1], w[2], w[3]));
-#pragma unroll
-            for (int db = 0; db < kD / 32; ++db)
-                oacc[db] = E::mfma(f[db], b, oacc[db]);
         }
+        if (kb == 1 && ++j_m == tiles_per_group) { j_m = 0; ++gi_m; }
     };
-    // Weights of key block kb against the current reference maximum; adds this lane's share of the
-    // row sum (taken over the rounded weights) to ls.  The packed dot product does the summing.
-    auto exp_half = [&](int kb, uint32_t (&pw)[2][8], float& ls) {
+    // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to be:
+    // the common path computes exp2(c*s - c*m_ref) without looking at the block's own maximum and
+    // checks afterwards that no row sum of the block left the safe range.  Only then (and on the
+    // first block, whose maximum is taken up front) is the true maximum computed, O and the running
+    // sum rescaled, and the block's weights recomputed.  Any reference gives the same quotient
+    // O / l; this one keeps every weight below 2^40, which bf16 and the fp32 accumulators hold
+    // without loss of relative accuracy.
+    auto block_max = [&](int kb) {
+        float mx = S[kb][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
+        return max_across_halves(mx);
+    };
+    auto refresh_reference = [&](int kb, float& ls) {   // the rare path
+        const float m_new = fmaxf(m_ref, block_max(kb));
+        const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);
+        m_ref = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
         const float mc = m_ref * c;
+        ls = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], c, -mc));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], c, -mc));
-            const uint32_t w = E::pack(p0, p1);
-            pw[kb][r >> 1] = w;
-            ls = E::add_pair(w, ls);
+            pw[kb][r >> 1] = E::pack(p0, p1);
+            ls += p0 + p1;
         }
-    };
-    auto mask_tail = [&]() {   // the ragged tile: keys past the end of their run get weight 0
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (key >= mask_valid) S[kb][r] = -INFINITY;
-            }
-    };
-    // kRagged: called once per KV tile, in walk order.  Keys of a border group's box that lie outside
-    // the grid get weight 0.  (The first tile of every box holds its first token, which is always
-    // inside, so the first tile of a walk never ends up without a finite score.)
-    int gi_m = 0, j_m = 0;   // list entry / tile-in-group of the tile whose scores are in S
-    const uint32_t full_box = pack_coord(geo.g[0] - 1, geo.g[1] - 1, geo.g[2] - 1);
-    auto mask_outside = [&]() {
-        const uint32_t lim = __builtin_amdgcn_readfirstlane(s_limit[min(gi_m, n_listed - 1)]);
-        if (lim != full_box) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int rq = 0; rq < 4; ++rq) {
-                    // accumulator registers 4*rq .. 4*rq+3 hold 4 consecutive keys
-                    const uint4 c = *(const uint4*)&s_coord[j_m * kBN + 32 * kb + 8 * rq + 4 * half];
-                    if (!coord_inside(c.x, lim)) S[kb][4 * rq] = -INFINITY;
-                    if (!coord_inside(c.y, lim)) S[kb][4 * rq + 1] = -INFINITY;
-                    if (!coord_inside(c.z, lim)) S[kb][4 * rq + 2] = -INFINITY;
-                    if (!coord_inside(c.w, lim)) S[kb][4 * rq + 3] = -INFINITY;
-                }
-        }
-        if (++j_m == tiles_per_group) { j_m = 0; ++gi_m; }
-    };
-    // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to be:
-    // the common path computes exp2(c*s - c*m_ref) without looking at the tile's own maximum and
-    // checks afterwards that no row sum of the tile left the safe range.  Only then (and on the
-    // first tile, where m_ref = -inf makes every sum infinite) is the true maximum computed, O and
-    // the running sum rescaled, and the tile's weights recomputed.  Any reference gives the same
-    // quotient O / l; this one keeps every weight below 2^40, which bf16 and the fp32 accumulators
-    // hold without loss of relative accuracy.
-    auto finish_softmax = [&](uint32_t (&pw)[2][8], float ls) {
-        if (__builtin_amdgcn_ballot_w64(!(ls < E::kSumLimit)) != 0) {
-            float mx = S[0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
-            mx = max_across_halves(mx);
-            const float m_new = fmaxf(m_ref, mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // first tile: 0
-            m_ref = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < kD / 32; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            ls = 0.f;
-            exp_half(0, pw, ls);
-            exp_half(1, pw, ls);
-        }
-        l_run += ls;
-    };
-
-    // First tile: there is no older reference, so the maximum is taken up front.
-    auto first_softmax = [&](uint32_t (&pw)[2][8]) {
-        float mx = S[0][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
-        m_ref = max_across_halves(mx);
-        float ls = 0.f;
-        exp_half(0, pw, ls);
-        exp_half(1, pw, ls);
-        l_run = ls;
     };
 
     // ---- prologue: K tile 0 -----------------------------------------------------------------
@@ -533,70 +478,153 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
 
     // swap_barrier(t) publishes K(t) and V(t-1), fetched during the previous tile, and frees the
     // buffers of K(t-1) and V(t-2), which are refilled with K(t+1) and V(t) right away.
+    // next_addrs(t): looks up where K(t+2) and V(t+1) lie (one tile before they are fetched, so that
+    // the table reads never sit between a barrier and the loads that follow it).
+    auto next_addrs = [&](int t) {
+        // (looked up unconditionally, also past the last tile, so that the table reads stay inside the
+        // straight-line block around them instead of becoming a block of their own with its own waits)
+        if (dense) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
+        else v_from_k(va, ka);   // tile t + 1, whose K part has just been asked for
+        tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
+    };
     auto swap_barrier = [&](int t) {
         __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
         if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka, k_on);
         if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
-        // (looked up unconditionally, also past the last tile, so that the table reads stay inside the
-        // straight-line block that follows instead of becoming a block of their own with its own waits)
-        if (dense) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
-        else v_from_k(va, ka);   // tile t + 1, whose K part has just been asked for
-        tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
     };
 
-    // tile 0: QK and weights only
+    // One step = the two half steps between two barriers, as one instruction stream.  Half KB (0, 1)
+    // works on keys 32*KB .. 32*KB+31 of its tiles.  Per half, QK: form S[KB] from the K tile in
+    // sK[kbuf]; SM: weights of the block whose scores are in S[KB ^ 1] (0 none, 1 against the current
+    // reference, 2 first block of the walk: the reference is its maximum); PV: O^T += V^T P^T for
+    // half KB of the V tile in sV[vbuf], with the weights in pw[KB].  check: the walk contains a tile
+    // with fewer than 64 valid keys; t_sm0 / t_sm1 = tile index of the block weighted in each half.
+    // The items (one MFMA each, with its fragment read kFragAhead items ahead) run in one rolling
+    // sequence over both halves; the vector chunks of a half are dealt out over its items.
+    auto step = [&](auto qk0_c, auto sm0_c, auto pv0_c, auto qk1_c, auto sm1_c, auto pv1_c, auto check, auto kbuf_c,
+                    int vbuf, int t_sm0, int t_sm1) {
+        constexpr int kbuf = decltype(kbuf_c)::value;
+        constexpr int SMm[2] = {decltype(sm0_c)::value, decltype(sm1_c)::value};
+        constexpr int NQ[2] = {decltype(qk0_c)::value ? D / 16 : 0, decltype(qk1_c)::value ? D / 16 : 0};
+        constexpr int NP[2] = {decltype(pv0_c)::value ? 2 * (D / 32) : 0, decltype(pv1_c)::value ? 2 * (D / 32) : 0};
+        constexpr int NI[2] = {NQ[0] + NP[0], NQ[1] + NP[1]};
+        constexpr int NT = NI[0] + NI[1], AHEAD = kFragAhead;
+        frag8 fr[NT > 0 ? NT : 1];
+        auto fetch = [&](int i) {
+            const int h = i < NI[0] ? 0 : 1, j = i - (h ? NI[0] : 0);
+            if (j < NQ[h]) fr[i] = k_frag(kbuf, h, j);
+            else fr[i] = v_frag(vbuf, h, (j - NQ[h]) / (D / 32), (j - NQ[h]) % (D / 32));
+        };
+        float mc = 0.f, ls0 = 0.f, ls1 = 0.f, t1[8], e0[8];
+        auto sm_begin = [&](int h) {   // h: the half; the block being weighted is h ^ 1
+            if (SMm[h] == 0) return;
+            const int sb = h ^ 1;
+            if constexpr (decltype(check)::value) {
+                if ((h ? t_sm1 : t_sm0) == mask_tile) mask_tail(sb);
+            }
+            if (MODE == kRagged) mask_outside(sb);
+            if (SMm[h] == 2) m_ref = block_max(sb);
+            mc = m_ref * c;
+        };
+        // two vector chunks per pair of scores: {fma, fma, exp2} and {exp2, pack, add, add}
+        auto sm_chunk = [&](int h, int ch) {
+            const int g = ch >> 1, sb = h ^ 1;
+            if ((ch & 1) == 0) {
+                const float t0 = fmaf(S[sb][2 * g], c, -mc);
+                t1[g] = fmaf(S[sb][2 * g + 1], c, -mc);
+                e0[g] = __builtin_amdgcn_exp2f(t0);
+            } else {
+                const float e1 = __builtin_amdgcn_exp2f(t1[g]);
+                pw[sb][g] = E::pack(e0[g], e1);
+                asm volatile("" : "+v"(pw[sb][g]));   // (keeps the conversion here: its first use is a block later)
+                ls0 = g == 0 ? e0[g] : ls0 + e0[g];
+                ls1 = g == 0 ? e1 : ls1 + e1;
+            }
+        };
+        auto sm_end = [&](int h) {
+            if (SMm[h] == 0) return;
+            float ls = ls0 + ls1;
+            if (SMm[h] == 1) {
+                if (__builtin_amdgcn_ballot_w64(!(ls < E::kSumLimit)) != 0) refresh_reference(h ^ 1, ls);
+            }
+            l_run += ls;
+        };
+        // first of the 16 chunks of half h that go with its item j
+        auto chunk_lo = [&](int h, int j) { return SMm[h] ? j * 16 / NI[h] : 0; };
+#pragma unroll
+        for (int a = 0; a < AHEAD && a < NT; ++a) fetch(a);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            sm_begin(h);
+            if (NI[h] == 0) {
+#pragma unroll
+                for (int ch = 0; ch < (SMm[h] ? 16 : 0); ++ch) sm_chunk(h, ch);
+            }
+#pragma unroll
+            for (int j = 0; j < NI[h]; ++j) {
+                const int i = (h ? NI[0] : 0) + j;
+                if (i + AHEAD < NT) fetch(i + AHEAD);
+                if (j < NQ[h]) {
+                    if (j == 0) {
+                        f32x16 zero;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+                        S[h] = E::mfma(fr[i], qf[j], zero);
+                    } else {
+                        S[h] = E::mfma(fr[i], qf[j], S[h]);
+                    }
+                } else {
+                    const int s2 = (j - NQ[h]) / (D / 32), db = (j - NQ[h]) % (D / 32);
+                    const uint32_t* w = &pw[h][4 * s2];
+                    const frag8 b = __builtin_bit_cast(frag8, make_uint4(w[0], w[1], w[2], w[3]));
+                    oacc[db] = E::mfma(fr[i], b, oacc[db]);
+                }
+#pragma unroll
+                for (int ch = chunk_lo(h, j); ch < chunk_lo(h, j + 1); ++ch) sm_chunk(h, ch);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            sm_end(h);
+        }
+    };
+    using std::integral_constant;
+    constexpr integral_constant<int, 0> c0{};
+    constexpr integral_constant<int, 1> c1{};
+    constexpr integral_constant<int, 2> c2{};
+    constexpr std::false_type no{};
+    constexpr std::true_type yes{};
+
+    // tile 0: both QK products, and the weights of its first block against that block's maximum
     {
         swap_barrier(0);
-        qk_half(0, 0);
-        qk_half(0, 1);
-        if (!kLists && mask_tile == 0) mask_tail();
-        if (MODE == kRagged) mask_outside();
-        first_softmax(pwA);
-    }
-    // tile t >= 1: QK(t), weights(t) and PV(t-1) in one straight-line block; the statement order
-    // below is only a hint, the instruction scheduler interleaves the three streams
-    // (check: a compile-time flag - the walk contains a tile with fewer than 64 valid keys.  Without
-    // it the step is one basic block; the test for that tile would split it after the QK product.)
-    auto tile_step = [&](auto check, int t, uint32_t (&pw_cur)[2][8], const uint32_t (&pw_prev)[2][8]) {
-        swap_barrier(t);
-        float ls = 0.f;
-        qk_half(t & 1, 0);
-        qk_half(t & 1, 1);
-        if constexpr (decltype(check)::value) {
-            if (t == mask_tile) mask_tail();
+        next_addrs(0);
+        if (!kLists && mask_tile == 0) {
+            step(yes, c0, no, no, c0, no, no, c0, 0, 0, 0);
+            mask_tail(0);
+            step(no, c0, no, yes, c2, no, no, c0, 0, 0, 0);
+        } else {
+            step(yes, c0, no, yes, c2, no, no, c0, 0, 0, 0);
         }
-        if (MODE == kRagged) mask_outside();
-        // From here on the step is a dependent chain of vector work with MFMAs of the previous tile
-        // in its gaps: the wave that is in it goes first, the SIMD's other wave fills in with its
-        // QK product (measured: +0.5 %; raising the QK part instead: -2 %).
-        __builtin_amdgcn_s_setprio(1);
-        exp_half(0, pw_cur, ls);
-        pv_half((t - 1) & 1, 0, pw_prev);
-        exp_half(1, pw_cur, ls);
-        pv_half((t - 1) & 1, 1, pw_prev);
-        finish_softmax(pw_cur, ls);
-        __builtin_amdgcn_s_setprio(0);
+    }
+    // tile t >= 1, first half: QK(t, keys 0..31), weights of (t-1, keys 32..63), PV of (t-1, keys 0..31);
+    // second half: QK(t, 32..63), weights of (t, 0..31), PV of (t-1, 32..63)
+    auto tile_step = [&](auto check, auto kbuf, int t) {   // kbuf = t & 1, as a compile-time constant
+        swap_barrier(t);
+        next_addrs(t);
+        step(yes, c1, yes, yes, c1, yes, check, kbuf, kbuf ^ 1, t - 1, t);
     };
     auto walk = [&](auto check) {
-        int t = 1;
+        int t = 1;   // (two steps per trip: the LDS buffers of every step are compile-time constants)
         for (; t + 1 < n_tiles; t += 2) {
-            tile_step(check, t, pwB, pwA);
-            tile_step(check, t + 1, pwA, pwB);
+            tile_step(check, c1, t);
+            tile_step(check, c0, t + 1);
         }
-        if (t < n_tiles) {
-            tile_step(check, t, pwB, pwA);
-            swap_barrier(n_tiles);
-            pv_half((n_tiles - 1) & 1, 0, pwB);
-            pv_half((n_tiles - 1) & 1, 1, pwB);
-        } else {
-            swap_barrier(n_tiles);
-            pv_half((n_tiles - 1) & 1, 0, pwA);
-            pv_half((n_tiles - 1) & 1, 1, pwA);
-        }
+        if (t < n_tiles) tile_step(check, c1, t);
+        swap_barrier(n_tiles);
+        step(no, c1, yes, no, c0, yes, check, c0, (n_tiles - 1) & 1, n_tiles - 1, n_tiles - 1);
     };
-    if (!kLists && mask_tile >= 1) walk(std::true_type{});   // (tile 0 was handled above)
-    else walk(std::false_type{});
+    if (!kLists && mask_tile >= 0) walk(yes);
+    else walk(no);
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
     // In the accumulator layout a lane holds 4 consecutive head dims (8 bytes) at a time of ITS
@@ -650,28 +678,42 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int tile, u
     }
 }
 
-// The kernel: picks this workgroup's query tile and runs it.  Tiles are handed out so that every
-// XCD works through one contiguous range of the tile order (see xcd_contiguous_tile); in joint
-// mode the long-running dense tiles over the prompt rows get the lowest block indices, dealt
-// round-robin over the XCDs, and behind them every XCD walks its range of grouped tiles.
+// The kernel: picks this workgroup's query tile and runs it.  Workgroups are dealt round-robin to the
+// 8 XCDs; block b runs on XCD b % 8 as that XCD's (b / 8)-th workgroup.  The XCDs walk the heads
+// TOGETHER: within a head every XCD owns one eighth of the head's tile order (a compact range of
+// query groups; which eighth rotates from head to head, so that the short lists of border groups are
+// spread evenly), so at any time the whole chip reads the K/V of one or two heads (which the memory-side
+// cache holds) and every XCD's L2 sees a compact patch of neighbouring groups.  In joint mode the
+// long-running dense tiles over the prompt rows get the lowest block indices, dealt round-robin over
+// the XCDs, and the grouped tiles follow.
+template <bool DENSE>
+__device__ __forceinline__ bool head_sync_tile(const AttnParams& p, int xcd, int idx, int& bh, int& t_in_head) {
+    const int per = DENSE ? p.per_xcd_dense : p.per_xcd;
+    const int tph = DENSE ? p.q_tiles_dense : p.geo.num_groups * p.q_tiles;
+    bh = (int)fdiv((uint32_t)idx, DENSE ? p.fd_per_xcd_dense : p.fd_per_xcd);
+    t_in_head = ((xcd + bh) % kNumXcd) * per + (idx - bh * per);   // (rotated per head: border groups have shorter lists)
+    return t_in_head < tph && bh < p.batch * p.heads;
+}
 template <int NWAVES, int MODE, bool F16, int D>
-__global__ __launch_bounds__(NWAVES * 64, 2) void attn_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
     __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
+    const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
+    int bh, t_in_head;
     if constexpr (MODE == kJoint) {
-        const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
         const int dense_per_xcd = (p.n_dense_tiles + kNumXcd - 1) / kNumXcd;
         if (idx < dense_per_xcd) {
             const int tile = idx * kNumXcd + xcd;
-            if (tile < p.n_dense_tiles) attn_tile<NWAVES, MODE, F16, D, true>(p, tile, sK, sV);
-        } else {
-            const int per = (p.total_tiles + kNumXcd - 1) / kNumXcd;
-            const int tile = xcd * per + (idx - dense_per_xcd);
-            if (idx - dense_per_xcd < per && tile < p.total_tiles) attn_tile<NWAVES, MODE, F16, D, false>(p, tile, sK, sV);
+            if (tile < p.n_dense_tiles) {
+                bh = (int)fdiv((uint32_t)tile, p.fd_tiles_per_head_dense);
+                attn_tile<NWAVES, MODE, F16, D, true>(p, bh, tile - bh * p.q_tiles_dense, sK, sV);
+            }
+        } else if (head_sync_tile<false>(p, xcd, idx - dense_per_xcd, bh, t_in_head)) {
+            attn_tile<NWAVES, MODE, F16, D, false>(p, bh, t_in_head, sK, sV);
         }
     } else {
-        const int tile = xcd_contiguous_tile(blockIdx.x, p.total_tiles);
-        if (tile < p.total_tiles) attn_tile<NWAVES, MODE, F16, D, MODE == kDense>(p, tile, sK, sV);
+        if (head_sync_tile<MODE == kDense>(p, xcd, idx, bh, t_in_head))
+            attn_tile<NWAVES, MODE, F16, D, MODE == kDense>(p, bh, t_in_head, sK, sV);
     }
 }
 
@@ -679,15 +721,17 @@ template <int NWAVES, bool F16, int D>
 inline hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
     const dim3 block(NWAVES * 64);
     const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * (mode == kRagged ? 2 : 1) * ((size_t)p.geo.group_tokens + p.max_kv);
+    const int bh = p.batch * p.heads;
+    const int grouped_blocks = kNumXcd * p.per_xcd * bh, dense_blocks = kNumXcd * p.per_xcd_dense * bh;
     if (mode == kRagged) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kRagged, F16, D>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kRagged, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
     } else if (mode == kDense) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kDense, F16, D>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kDense, F16, D>), dim3(dense_blocks), block, dyn, stream, p);
     } else if (mode == kGrouped) {
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kGrouped, F16, D>), dim3(xcd_padded_blocks(p.total_tiles)), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kGrouped, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
     } else {
-        const int blocks = xcd_padded_blocks(p.n_dense_tiles) + xcd_padded_blocks(p.total_tiles);
-        hipLaunchKernelGGL((attn_bf16_kernel<NWAVES, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
+        const int blocks = xcd_padded_blocks(p.n_dense_tiles) + grouped_blocks;
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
     }
     return hipGetLastError();
 }

@@ -150,7 +150,10 @@ extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid,
 // Divisors of the MFMA kernel's index decompositions, from the finished launch parameters.
 static void fill_fastdivs(AttnParams& p) {
     const Geometry& geo = p.geo;
-    p.fd_tiles_per_head = make_fastdiv((uint32_t)geo.num_groups * (uint32_t)p.q_tiles);
+    p.per_xcd = (geo.num_groups * p.q_tiles + kNumXcd - 1) / kNumXcd;
+    p.per_xcd_dense = (p.q_tiles_dense + kNumXcd - 1) / kNumXcd;
+    p.fd_per_xcd = make_fastdiv((uint32_t)p.per_xcd);
+    p.fd_per_xcd_dense = make_fastdiv((uint32_t)p.per_xcd_dense);
     p.fd_tiles_per_head_dense = make_fastdiv((uint32_t)p.q_tiles_dense);
     p.fd_heads = make_fastdiv((uint32_t)p.heads);
     p.fd_q_tiles = make_fastdiv((uint32_t)p.q_tiles);
@@ -227,8 +230,9 @@ static grat_status attention_fwd(const void* Q, const void* K, const void* V, vo
     }
     p.q_tiles = (n_g + bm - 1) / bm;
     p.strip_w = geo.G[2] >= 16 ? 8 : geo.G[2];
+    // (the launch pads every head's tiles to a multiple of 8: up to 7 more per head)
     const int64_t total = (int64_t)batch * heads * geo.num_groups * p.q_tiles;
-    if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
+    if ((int64_t)batch * heads * ((int64_t)geo.num_groups * p.q_tiles + 8) >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
     int mode = ragged ? kRagged : kGrouped;
@@ -322,7 +326,7 @@ extern "C" grat_status grat_dense_attention_fwd(const void* Q, const void* K, co
     p.n_dense_rows = (int32_t)n_tokens;
     p.dense_row0 = 0;
     const int64_t total = (int64_t)batch * heads * p.q_tiles;
-    if (total >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
+    if ((int64_t)batch * heads * ((int64_t)p.q_tiles + 8) >= kMaxElems - 8) return GRAT_ERR_UNSUPPORTED;
     p.total_tiles = (int32_t)total;
 
     fill_fastdivs(p);

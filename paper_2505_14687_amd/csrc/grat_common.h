@@ -47,9 +47,10 @@ struct AttnParams {
     int32_t global_row0;       // first prompt row
     int32_t grid_row0;         // first grid row
     // MFMA kernel: host-prepared divisors for the index decompositions of its prologue
-    FastDiv fd_tiles_per_head;        // by num_groups * q_tiles (grouped tiles)
     FastDiv fd_tiles_per_head_dense;  // by q_tiles_dense
     FastDiv fd_heads, fd_q_tiles;
+    int32_t per_xcd, per_xcd_dense;   // tiles of one head that one XCD owns: ceil(tiles per head / 8), grouped and dense
+    FastDiv fd_per_xcd, fd_per_xcd_dense;
     FastDiv fd_strip, fd_strip_w, fd_strip_tail;   // strip order: by rows * strip_w, strip_w, width of the last strip
     int32_t strip_full;               // full strips: cols / strip_w
     FastDiv fd_g1, fd_g2, fd_G1, fd_G2;            // token in group -> box coordinates, group id -> group coordinates
@@ -74,9 +75,9 @@ hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern 
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, bool dense, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams& p, int mode /* AttnMode */, bool f16, int head_dim, hipStream_t stream);
 
-// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD one
-// contiguous range of the logical tile order instead, so that tiles sharing K/V meet in one L2.
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).
 constexpr int kNumXcd = 8;
+// fp32 kernel: every XCD gets one contiguous range of the logical tile order.
 __device__ __forceinline__ int xcd_contiguous_tile(int block, int total) {
     const int per = (total + kNumXcd - 1) / kNumXcd;
     return (block % kNumXcd) * per + block / kNumXcd;   // may be >= total: caller exits
