@@ -20,8 +20,8 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 
 def measured_traffic(workload, pattern):
     """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one
-    for this workload (profiles/attn_bf16_<workload>_<pattern>.md, line 'traffic_bytes_per_launch: N')."""
-    path = os.path.join(ROOT, "profiles", f"attn_bf16_{workload}_{pattern}.md")
+    for this workload (profiles/attn_mfma_<workload>_<pattern>.md, line 'traffic_bytes_per_launch: N')."""
+    path = os.path.join(ROOT, "profiles", f"attn_mfma_{workload}_{pattern}.md")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -141,6 +141,7 @@ def main():
         extra[label] = {"ms_per_step": round(r["ms_per_step"], 4),
                         "attn_kernel_ms_avg": round(r["attn_kernel_ms_avg"], 4),
                         "tflops": round(r["flops"] / (r["attn_kernel_ms_avg"] * 1e-3) / 1e12, 2),
+                        "frac_of_peak": round(r["flops"] / (r["attn_kernel_ms_avg"] * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS, 4),
                         "attended_pairs": r["pairs"]}
         log(f"{label}: {extra[label]}")
 
@@ -189,6 +190,48 @@ def main():
         except Exception as e:   # noqa: BLE001
             log(f"MFMA-only probe failed: {e!r}")
 
+    # the other benchmark configurations, one line each (attention launch only, lists prebuilt; inputs
+    # N(0,1) rounded to bf16 like the main workload's, drawn on the device from a seeded generator)
+    others_w = {}
+    if not args.no_others and not args.constant_data and not n_glob and args.workload == "img8192":
+        for name, labels in (("img1024", ("B3", "X")), ("img2048", ("B3", "B5", "X", "dense")), ("video", ("B3", "X"))):
+            ww = synth.WORKLOADS[name]
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(ww.seed)
+            shape = (ww.batch, ww.heads, ww.n_tokens, ww.head_dim)
+            q, k, v = (torch.randn(shape, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+            o = torch.empty_like(q)
+            n_gw = int(np.prod(ww.group))
+            res = {}
+            for label in labels:
+                pat, rad = ww.patterns[label]
+                if pat == "dense":
+                    fn = lambda: grat.grat_dense_attention_fwd(q, k, v, ww.scale, out=o)
+                    pairs_w = ww.n_tokens * ww.n_tokens
+                else:
+                    cnt, idx = grat.grat_build_block_lists(ww.grid, ww.group, pat, rad)
+                    fn = lambda: grat.grat_attention_fwd(q, k, v, ww.scale, ww.grid, ww.group, cnt, idx, out=o)
+                    pairs_w = int(cnt.sum().item()) * n_gw * n_gw
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                times = []
+                for _ in range(10):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(); fn(); b.record()
+                    torch.cuda.synchronize()
+                    times.append(a.elapsed_time(b))
+                ms = float(np.median(times))
+                fl = 4.0 * ww.head_dim * ww.heads * ww.batch * pairs_w
+                res[label] = {"kernel_ms": round(ms, 4), "tflops": round(fl / (ms * 1e-3) / 1e12, 1)}
+            if "dense" in res:
+                for label in labels:
+                    if label != "dense":
+                        res[label]["speedup_vs_dense"] = round(res["dense"]["kernel_ms"] / res[label]["kernel_ms"], 2)
+            others_w[name] = res
+            log(f"{name}: {res}")
+            del q, k, v, o
+
     cpu = None
     if not args.no_cpu:
         import psutil
@@ -235,6 +278,7 @@ def main():
                "parity_rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(want))}
         log(f"cpu oracle: {cpu}")
 
+    traffic = None if n_glob or args.constant_data else measured_traffic(args.workload, args.pattern)
     out = {
         "metric": "GRAT attn TFLOP/s (attended pairs) + speedup vs dense attn, 1 MI355X",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -249,9 +293,12 @@ def main():
                    "step": "grat_build_block_lists + " + ("grat_attention_global_fwd" if n_glob else "grat_attention_fwd")},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
-                     "traffic": None if n_glob else measured_traffic(args.workload, args.pattern),
+                     "traffic": traffic,
+                     "traffic_source": None if traffic is None else
+                                       f"profiles/attn_mfma_{args.workload}_{args.pattern}.md: stored figure of a separate "
+                                       "rocprofv3 --pmc run of this command, not measured in this run",
                      # template arguments: waves per workgroup, mode (0 grouped, 2 joint), half?, head_dim
-                     "kernel": "grat::attn_bf16_kernel<%d, %d, false, %d>" % (
+                     "kernel": "grat::attn_mfma_kernel<%d, %d, false, %d>" % (
                          8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
                      # the same matrix instruction in a register-resident loop on this machine (operands
                      # with full significands spread like N(0,1); then all ones), and `achieved` as a
@@ -267,6 +314,7 @@ def main():
         "speedup_vs_dense": round(dense["kernel_ms"] / main_r["attn_kernel_ms_avg"], 2) if dense else None,
         "paper_context": "paper: GRAT-B 35.8x over full attention at 8192x8192 on one NVIDIA A100",
         "other_patterns": extra,
+        "other_workloads": others_w,
     }
     print(json.dumps(out), flush=True)
 

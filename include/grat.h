@@ -1,7 +1,7 @@
 /*
  * libgrat — GRAT grouped sparse attention (forward) for AMD MI355X (gfx950), C ABI.
  *
- * The method ("Grouping First, Attending Smartly", Sec. 3.2): image or video tokens laid out
+ * The method (GRAT, arXiv 2505.14687, Sec. 3.2): image or video tokens laid out
  * row-major over a 2D / 3D grid are partitioned into non-overlapping groups (Eq. 2-4, 9-11);
  * every query of a group attends the same set of key/value groups — the surrounding blocks
  * (GRAT-B, Eq. 5-6 / 12-13) or the criss-cross region (GRAT-X, Eq. 7-8 / 14-15) — and the
@@ -95,6 +95,26 @@ grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int3
                                    void* hip_stream);
 
 /*
+ * Check block lists against the format grat_build_block_lists writes, on the GPU: for callers that
+ * make their own lists (any set of KV groups per query group is a valid instance of the attendable
+ * sets of Sec. 3.2, Eq. 5-8 / 12-15, as long as it has this format).  The attention entry points do
+ * not check lists themselves; they only force counts and entries into range.
+ *   d_kv_count[G], d_kv_index[G * max_kv]  (device, in) the lists, G = prod ceil(grid[k] / group[k])
+ *   d_status[1]  (device, out) 0 if every list is well formed, else the OR of
+ *                GRAT_LIST_BAD_COUNT    a count outside [1, max_kv]
+ *                GRAT_LIST_BAD_ENTRY    a used entry outside [0, G)
+ *                GRAT_LIST_BAD_PADDING  an entry behind a list's count that is not -1
+ *                (order of the entries is not checked: any order gives the same attention result)
+ * Errors: GRAT_ERR_NULL, the geometry errors of grat_block_list_shape, GRAT_ERR_BUFFER_TOO_SMALL
+ * (max_kv < 1), GRAT_ERR_HIP.  Asynchronous on hip_stream (two small launches, no memset, nothing
+ * allocated): read d_status after synchronising with the stream.
+ */
+enum { GRAT_LIST_BAD_COUNT = 1, GRAT_LIST_BAD_ENTRY = 2, GRAT_LIST_BAD_PADDING = 4 };
+grat_status grat_validate_block_lists(int32_t ndim, const int32_t* grid, const int32_t* group,
+                                      const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                      int32_t max_kv, int32_t* d_status, void* hip_stream);
+
+/*
  * O = softmax(scale * Q K^T restricted to the block lists) V, per batch and head
  * (Sec. 3.1 Eq. 1 over the attendable sets of Sec. 3.2).
  *   Q, K, V (device, in), O (device, out): `dtype` elements, addressed with the strides
@@ -107,8 +127,10 @@ grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid, const int3
  *                          writes them for the same grid and group)
  *   d_kv_count, d_kv_index, max_kv   lists in the format grat_build_block_lists writes (the
  *                          caller may also supply its own).  Every used entry must lie in
- *                          [0, G) and every count in [1, max_kv]; the kernel does not check
- *                          them and an entry outside that range is undefined behaviour.
+ *                          [0, G) and every count in [1, max_kv]: the result for a list that
+ *                          breaks this is undefined (the kernels force counts and entries into
+ *                          range so that no access leaves the tensors, nothing more);
+ *                          grat_validate_block_lists checks a list on the GPU.
  * Supported (GRAT_ERR_UNSUPPORTED otherwise):
  *   GRAT_BF16, GRAT_F16: head_dim 128 or 64, tokens per (whole) group a multiple of 64; with clipped border
  *              groups also group[k] <= 1024 on the last two axes;

@@ -15,9 +15,9 @@ What it follows (paper sections / equations, numbered in order of appearance):
   * Sec. 3.2, Eq. 9-11     3D grouping with (t // g1, i // g2, j // g3);
   * Sec. 3.2, Eq. 12-13    3D GRAT-B with per-axis radii (b_t, b_h, b_w);
   * Sec. 3.2, Eq. 14-15    3D GRAT-X.  Printed predicate: at least ONE group coordinate
-                           equal (three planes) -> pattern "cross_planes".  The prose
-                           ("along its temporal, vertical and horizontal axes") is the
-                           three axis lines: at least ndim-1 coordinates equal ->
+                           equal (three planes) -> pattern "cross_planes".  The prose of
+                           Sec. 3.2 ahead of Eq. 14-15 describes the three axis lines
+                           through the group: at least ndim-1 coordinates equal ->
                            pattern "cross".  In 2D the two coincide.
 
 Readings where the paper is silent: neighbours outside the grid are dropped (no wrap, no

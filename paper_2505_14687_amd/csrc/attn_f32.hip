@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
         const int t = (t_in_head % p.q_tiles) * 64 + lane;
         q_valid = t < qb.tokens;
         q_row = token_row(qb, q_valid ? t : 0);
-        n_lists = p.kv_count[gamma];
+        n_lists = min(max(p.kv_count[gamma], 0), p.max_kv);   // (forced into range: a bad list never reads outside the tensors)
         list_tokens = 0;   // per listed group, below
     }
     if (!q_valid && DENSE) q_row = p.n_tokens - 1;
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnParams p) {
     for (int li = 0; li < n_lists; ++li) {
         Box kb{0, 1, 1, 0};
         if (!DENSE) {
-            kb = group_box(p.kv_index[(int64_t)gamma * p.max_kv + li]);
+            kb = group_box(min(max(p.kv_index[(int64_t)gamma * p.max_kv + li], 0), p.geo.num_groups - 1));
             list_tokens = kb.tokens;
         }
         for (int t0 = 0; t0 < list_tokens; t0 += kF32Keys) {

@@ -239,9 +239,11 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
             s_rowbytes[t] = (uint32_t)(c0 * T12 + c1 * geo.T[2] + c2) * row_pitch;
             if (MODE == kRagged) s_coord[t] = pack_coord(c0, c1, c2);
         }
-        const int cnt = p.kv_count[gamma];
+        // (a caller-made list is taken as it is, but its count and entries are forced into range: a
+        // bad list then gives wrong numbers, never an access outside the tables or the tensors)
+        const int cnt = min(max(p.kv_count[gamma], 0), p.max_kv);
         for (int i = tid; i < cnt; i += NT) {
-            const int gid = p.kv_index[(int64_t)gamma * p.max_kv + i];
+            const int gid = min(max(p.kv_index[(int64_t)gamma * p.max_kv + i], 0), geo.num_groups - 1);
             int p0, p1, p2;
             s_origin[i] = grid_base + (uint32_t)group_origin((uint32_t)gid, p0, p1, p2);
             if (MODE == kRagged) s_limit[i] = box_limit(gid);

@@ -53,6 +53,35 @@ __global__ __launch_bounds__(64) void build_block_lists_kernel(ListParams p) {
     if (lane == 0) p.kv_count[gamma] = cnt;
 }
 
+// Checks lists against the format above: one wave per query group; violations are OR-ed into
+// *status (cleared by a one-thread launch ahead of this one, so no host-side memset is involved).
+__global__ void clear_status_kernel(int32_t* status) { *status = 0; }
+__global__ __launch_bounds__(64) void validate_block_lists_kernel(const int32_t* kv_count, const int32_t* kv_index,
+                                                                  int32_t num_groups, int32_t max_kv, int32_t* status) {
+    const int gamma = blockIdx.x, lane = threadIdx.x;
+    const int cnt = kv_count[gamma];
+    int bad = (cnt < 1 || cnt > max_kv) ? GRAT_LIST_BAD_COUNT : 0;
+    const int used = min(max(cnt, 0), max_kv);
+    const int32_t* row = kv_index + (int64_t)gamma * max_kv;
+    for (int i = lane; i < max_kv; i += 64) {
+        const int v = row[i];
+        if (i < used) {
+            if (v < 0 || v >= num_groups) bad |= GRAT_LIST_BAD_ENTRY;
+        } else if (v != -1) {
+            bad |= GRAT_LIST_BAD_PADDING;
+        }
+    }
+    if (bad) atomicOr(status, bad);
+}
+
+hipError_t launch_validate_block_lists(const Geometry& geo, const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                       int32_t max_kv, int32_t* d_status, hipStream_t stream) {
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, stream, d_status);
+    hipLaunchKernelGGL(validate_block_lists_kernel, dim3(geo.num_groups), dim3(64), 0, stream, d_kv_count, d_kv_index,
+                       geo.num_groups, max_kv, d_status);
+    return hipGetLastError();
+}
+
 hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern pattern,
                                     const int32_t radius[3], int32_t* d_kv_count,
                                     int32_t* d_kv_index, int32_t max_kv, hipStream_t stream) {

@@ -147,6 +147,20 @@ extern "C" grat_status grat_build_block_lists(int32_t ndim, const int32_t* grid,
     return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
 }
 
+extern "C" grat_status grat_validate_block_lists(int32_t ndim, const int32_t* grid, const int32_t* group,
+                                                 const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                                 int32_t max_kv, int32_t* d_status, void* hip_stream) {
+    if (!d_kv_count || !d_kv_index || !d_status) return GRAT_ERR_NULL;
+    Geometry geo;
+    const grat_status st = make_geometry(ndim, grid, group, &geo);
+    if (st != GRAT_OK) return st;
+    if (max_kv < 1) return GRAT_ERR_BUFFER_TOO_SMALL;
+    if ((int64_t)geo.num_groups * max_kv >= kMaxElems) return GRAT_ERR_UNSUPPORTED;
+    const hipError_t e = launch_validate_block_lists(geo, d_kv_count, d_kv_index, max_kv, d_status,
+                                                     (hipStream_t)hip_stream);
+    return e == hipSuccess ? GRAT_OK : GRAT_ERR_HIP;
+}
+
 // Divisors of the MFMA kernel's index decompositions, from the finished launch parameters.
 static void fill_fastdivs(AttnParams& p) {
     const Geometry& geo = p.geo;

@@ -72,6 +72,8 @@ enum AttnMode : int { kGrouped = 0, kDense = 1, kJoint = 2, kRagged = 3 };
 hipError_t launch_build_block_lists(const Geometry& geo, int ndim, grat_pattern pattern,
                                     const int32_t radius[3], int32_t* d_kv_count,
                                     int32_t* d_kv_index, int32_t max_kv, hipStream_t stream);
+hipError_t launch_validate_block_lists(const Geometry& geo, const int32_t* d_kv_count, const int32_t* d_kv_index,
+                                       int32_t max_kv, int32_t* d_status, hipStream_t stream);
 hipError_t launch_attn_f32(const AttnParams& p, int head_dim, bool dense, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnParams& p, int mode /* AttnMode */, bool f16, int head_dim, hipStream_t stream);
 

@@ -106,6 +106,62 @@ def test_binding_rejects_host_tensors():
         grat.grat_dense_attention_fwd(x, x, x, 0.1, out=torch.zeros_like(x))
 
 
+def test_binding_checks_sequence_length_and_lists():
+    """The binding refuses what would make the kernels read past a tensor or misread a list: a
+    sequence that is not prod(grid) (+ n_global) rows long, lists that are not int32 / contiguous /
+    [G] and [G, max_kv].  (Host tensors: every one of these checks comes before the device check.)"""
+    import torch
+    grid, group = (64, 64), (16, 16)
+    x = torch.zeros(1, 2, 4096, 128, dtype=torch.bfloat16)
+    cnt = torch.zeros(16, dtype=torch.int32)
+    idx = torch.zeros(16, 9, dtype=torch.int32)
+    def plain(q=x, c=cnt, i=idx, g=grid):
+        return grat.grat_attention_fwd(q, q, q, 0.1, g, group, c, i, out=torch.zeros_like(q))
+    with pytest.raises(ValueError, match="sequence length"):
+        plain(g=(64, 128))                                   # grid larger than the tensor
+    with pytest.raises(ValueError, match="sequence length"):
+        plain(q=torch.zeros(1, 2, 4100, 128, dtype=torch.bfloat16))
+    with pytest.raises(ValueError, match="int32"):
+        plain(c=cnt.to(torch.int64))
+    with pytest.raises(ValueError, match="int32"):
+        plain(i=idx.to(torch.int64))
+    with pytest.raises(ValueError, match="contiguous"):
+        plain(i=torch.zeros(9, 16, dtype=torch.int32).t())
+    with pytest.raises(ValueError, match="kv_count"):
+        plain(c=torch.zeros(15, dtype=torch.int32))
+    with pytest.raises(ValueError, match="kv_index"):
+        plain(i=torch.zeros(15, 9, dtype=torch.int32))
+    with pytest.raises(ValueError, match="kv_index"):
+        plain(i=torch.zeros(16 * 9, dtype=torch.int32))
+    with pytest.raises(ValueError, match="device memory"):
+        plain()                                              # all shapes right: the host tensors themselves
+    # joint and packed entry points: n_global counts
+    xj = torch.zeros(1, 2, 4096 + 100, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="sequence length"):
+        grat.grat_attention_global_fwd(xj, xj, xj, 0.1, 99, True, grid, group, cnt, idx, out=torch.zeros_like(xj))
+    with pytest.raises(ValueError, match="device memory"):
+        grat.grat_attention_global_fwd(xj, xj, xj, 0.1, 100, True, grid, group, cnt, idx, out=torch.zeros_like(xj))
+    qkv = torch.zeros(1, 4096, 3, 2, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="sequence length"):
+        grat.grat_attention_packed_fwd(qkv, 0.1, (64, 60), group, cnt, idx)
+    with pytest.raises(ValueError, match="int32"):
+        grat.grat_attention_packed_fwd(qkv, 0.1, grid, group, cnt.to(torch.int16), idx)
+    with pytest.raises(ValueError, match="device memory"):
+        grat.grat_attention_packed_fwd(qkv, 0.1, grid, group, cnt, idx)
+
+
+def test_validate_block_lists_argument_errors():
+    L = grat.lib()
+    i32x2 = ctypes.c_int32 * 2
+    fake = 0x1000
+    def call(cnt=fake, idx=fake, status=fake, max_kv=9, grid=(64, 64), group=(16, 16), ndim=2):
+        return L.grat_validate_block_lists(ndim, i32x2(*grid), i32x2(*group), cnt, idx, max_kv, status, None)
+    assert call(cnt=None) == 1 and call(idx=None) == 1 and call(status=None) == 1
+    assert call(ndim=4) == 2
+    assert call(grid=(64, 0)) == 2
+    assert call(max_kv=0) == 5
+
+
 def test_joint_sequence_argument_errors():
     L = grat.lib()
     i32x2 = ctypes.c_int32 * 2

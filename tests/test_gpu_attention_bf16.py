@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import paper_2505_14687_amd as grat
-from gpu_util import assert_close, gather_rows, to_device, to_f64
+from gpu_util import assert_all_written, assert_close, gather_rows, nan_like, to_device, to_f64
 from oracle import grat_oracle as orc
 from paper_2505_14687_amd import synth
 
@@ -32,12 +32,16 @@ def workload_on_device(name, q_gain=1.0):
 
 
 def run_pattern(w, dev, pattern, radius):
+    """Runs into a NaN-filled output and checks that every element was stored (the sampled-row
+    tests below would not see a query tile that no workgroup took)."""
+    O = nan_like(dev[0])
     if pattern == "dense":
-        O = grat.grat_dense_attention_fwd(*dev, w.scale)
+        grat.grat_dense_attention_fwd(*dev, w.scale, out=O)
     else:
         count, index = grat.grat_build_block_lists(w.grid, w.group, pattern, radius)
-        O = grat.grat_attention_fwd(*dev, w.scale, w.grid, w.group, count, index)
+        grat.grat_attention_fwd(*dev, w.scale, w.grid, w.group, count, index, out=O)
     torch.cuda.synchronize()
+    assert_all_written(O, f"{pattern} {w.grid}")
     return O
 
 
@@ -101,8 +105,9 @@ def test_video_sampled_rows(label):
 # ---- beyond the five configs: the paper's video shape and its group-size / radius ablation ------
 @pytest.mark.parametrize("name,label", [
     ("video_paper", "B3"), ("video_paper", "X"), ("video_paper", "Xplanes"),
-    ("img8192_g8", "B3"), ("img8192_g8", "B7"), ("img8192_g8", "X"),
+    ("img8192_g8", "B3"), ("img8192_g8", "B5"), ("img8192_g8", "B7"), ("img8192_g8", "X"),
     ("img8192_g32", "B3"), ("img8192_g32", "X"),
+    ("img8192_b2", "B5"),
 ])
 def test_paper_shapes_sampled_rows(name, label):
     w, host, dev = workload_on_device(name)
@@ -281,3 +286,28 @@ def test_largest_group_4096_tokens():
     """4096 tokens per group (the limit of the in-LDS offset table): 16 query tiles per group."""
     got, want = small_case(1, 2, (128, 64), (64, 64), "block", (1, 0), seed=97)
     assert_close(got, want, "bf16", "4096-token groups")
+
+
+def test_out_of_range_list_entries_are_forced_into_range():
+    """A caller-made list that breaks the contract (count beyond the row, entries outside [0, G)) is
+    read as the list with its count and entries forced into range: every access stays inside the
+    tensors and the result is that of the repaired list."""
+    grid, group = (64, 64), (16, 16)
+    host = synth.make_qkv(1, 2, 4096, 128, "bf16", 93)
+    dev = [to_device(x) for x in host]
+    scale = 1.0 / math.sqrt(128)
+    count, index = grat.grat_build_block_lists(grid, group, "block", (1, 1))
+    G, max_kv = index.shape
+    bad_c, bad_i = count.clone(), index.clone()
+    bad_c[5] = max_kv + 7                 # interior group: its row is full, so the forced count reads the same 9 entries
+    bad_i[0, 1] = G + 100                 # -> G - 1
+    bad_i[3, 0] = -12                     # -> 0
+    fix_c, fix_i = count.clone(), index.clone()
+    fix_i[0, 1] = G - 1
+    fix_i[3, 0] = 0
+    assert grat.grat_validate_block_lists(grid, group, bad_c, bad_i).item() == 3
+    assert grat.grat_validate_block_lists(grid, group, fix_c, fix_i).item() == 0
+    a = grat.grat_attention_fwd(*dev, scale, grid, group, bad_c, bad_i)
+    b = grat.grat_attention_fwd(*dev, scale, grid, group, fix_c, fix_i)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import paper_2505_14687_amd as grat
-from gpu_util import assert_close, gather_rows, to_device, to_f64
+from gpu_util import assert_all_written, assert_close, gather_rows, nan_like, to_device, to_f64
 from oracle import grat_oracle as orc
 from paper_2505_14687_amd import synth
 
@@ -16,8 +16,10 @@ pytestmark = pytest.mark.gpu
 def run_joint(host, n_global, global_first, grid, group, pattern, radius, scale):
     dev = [to_device(x) for x in host]
     count, index = grat.grat_build_block_lists(grid, group, pattern, radius)
-    O = grat.grat_attention_global_fwd(*dev, scale, n_global, global_first, grid, group, count, index)
+    O = nan_like(dev[0])
+    grat.grat_attention_global_fwd(*dev, scale, n_global, global_first, grid, group, count, index, out=O)
     torch.cuda.synchronize()
+    assert_all_written(O, f"joint {n_global} {grid} {pattern}")
     return O
 
 
@@ -66,3 +68,22 @@ def test_joint_image_scale_sampled_rows(label, global_first):
     want = orc.joint_attention_rows(*host, samples, n_global, global_first, w.grid, w.group, pattern,
                                     radius, w.scale)
     print(label, assert_close(gather_rows(O, samples), want, "bf16", f"joint img2048 {label}"))
+
+
+@pytest.mark.parametrize("label,global_first", [("B3", True), ("X", True)])
+def test_joint_paper_scale_sampled_rows(label, global_first):
+    """512x512 tokens + 512 prompt tokens, 24 heads (the sequence Tab. 1 / Tab. 6 were measured on,
+    by their printed GRAT-X sparsities): sampled rows incl. prompt rows and the grid's corners."""
+    w = synth.WORKLOADS["img8192"]
+    pattern, radius = w.patterns[label]
+    n_global = 512
+    L = n_global + w.n_tokens
+    host = synth.make_qkv(w.batch, w.heads, L, w.head_dim, "bf16", 1011, threads=16)
+    O = run_joint(host, n_global, global_first, w.grid, w.group, pattern, radius, w.scale)
+    samples = synth.sample_rows(2008, 512, w.batch, w.heads, L)
+    samples[:32, 2] = np.arange(32) * 16              # prompt rows
+    samples[32:36, 2] = [n_global, L - 1, n_global + 511, n_global + 511 * 512]
+    want = orc.joint_attention_rows(*host, samples, n_global, global_first, w.grid, w.group, pattern,
+                                    radius, w.scale)
+    del host
+    print(label, assert_close(gather_rows(O, samples), want, "bf16", f"joint img8192 {label}"))

@@ -54,3 +54,30 @@ def test_rebuild_is_deterministic():
     b = grat.grat_build_block_lists((30, 48, 80), (2, 8, 8), "cross_planes")
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_validate_block_lists_flags():
+    """grat_validate_block_lists through the C ABI: 0 for the builder's own lists (also with a wider
+    row pitch), and the flag of every kind of damage planted in a copy of them."""
+    from paper_2505_14687_amd.grat import LIST_BAD_COUNT, LIST_BAD_ENTRY, LIST_BAD_PADDING
+    for grid, group, pattern, radius in [((128, 128), (16, 16), "block", (1, 1)), ((30, 48, 80), (2, 8, 8), "cross", None),
+                                         ((70, 50), (16, 16), "cross_planes", None)]:
+        G, need = grat.grat_block_list_shape(grid, group, pattern, radius)
+        for max_kv in (need, need + 5):
+            count, index = grat.grat_build_block_lists(grid, group, pattern, radius, max_kv=max_kv)
+            assert grat.grat_validate_block_lists(grid, group, count, index).item() == 0
+            def damaged(edit):
+                c, i = count.clone(), index.clone()
+                edit(c, i)
+                return grat.grat_validate_block_lists(grid, group, c, i).item()
+            def zero_count(c, i): c[G // 2] = 0
+            def long_count(c, i): c[G - 1] = max_kv + 1
+            def entry_past_end(c, i): i[3, 0] = G
+            def negative_entry(c, i): i[0, 1] = -1
+            def dirty_padding(c, i): i[0, max_kv - 1] = 0        # (a corner group: its list is shorter than the row)
+            assert damaged(zero_count) & LIST_BAD_COUNT
+            assert damaged(long_count) & LIST_BAD_COUNT
+            assert damaged(entry_past_end) == LIST_BAD_ENTRY
+            assert damaged(negative_entry) == LIST_BAD_ENTRY
+            if int(count[0]) < max_kv:
+                assert damaged(dirty_padding) == LIST_BAD_PADDING

@@ -60,36 +60,3 @@ def test_graph_replays_match_eager(grid, group, pattern, radius, n_global):
         enqueue()                   # eager, same inputs
         torch.cuda.synchronize()
         assert torch.equal(got, O), f"replay {rep}"
-
-
-def test_side_stream_is_the_launch_stream():
-    """Work is enqueued on the stream the caller names and ordered with what that stream already
-    holds: inputs written by copies on a side stream (default priority) are what the kernels read,
-    and the result equals a run on the default stream bit for bit."""
-    grid, group = (64, 64), (16, 16)
-    scale = 1.0 / math.sqrt(128)
-    host = [to_device(x) for x in synth.make_qkv(1, 4, 4096, 128, "bf16", 410)]
-    count, index = grat.grat_build_block_lists(grid, group, "cross", (0, 0))
-    want = grat.grat_attention_fwd(*host, scale, grid, group, count, index)
-    torch.cuda.synchronize()
-    side = torch.cuda.Stream()
-    Q, K, V = (torch.zeros_like(t) for t in host)
-    O = torch.zeros_like(Q)
-    torch.cuda.synchronize()
-    with torch.cuda.stream(side):
-        for dst, src in zip((Q, K, V), host):
-            dst.copy_(src, non_blocking=True)
-        c2, i2 = grat.grat_build_block_lists(grid, group, "cross", (0, 0), stream=side)
-        grat.grat_attention_fwd(Q, K, V, scale, grid, group, c2, i2, out=O, stream=side)
-    side.synchronize()
-    assert torch.equal(O, want)
-
-
-@pytest.mark.parametrize("data", ["ones", "small_ints", "normal_like"])
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
-def test_mfma_probe_does_its_work(dtype, data):
-    from paper_2505_14687_amd.probe import probe_wave_sum
-    sink = grat.grat_probe_mfma(dtype, data, 512, 64)
-    torch.cuda.synchronize()
-    assert sink.shape == (512 * 256,)
-    assert torch.all(sink.view(-1, 64).sum(1) == probe_wave_sum(data, 64))
