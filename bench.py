@@ -297,8 +297,8 @@ def main():
                      "traffic_source": None if traffic is None else
                                        f"profiles/attn_mfma_{args.workload}_{args.pattern}.md: stored figure of a separate "
                                        "rocprofv3 --pmc run of this command, not measured in this run",
-                     # template arguments: waves per workgroup, mode (0 grouped, 2 joint), half?, head_dim
-                     "kernel": "grat::attn_mfma_kernel<%d, %d, false, %d>" % (
+                     # template arguments: waves per workgroup, keys per LDS tile, mode (0 grouped, 2 joint), half?, head_dim
+                     "kernel": "grat::attn_mfma_kernel<%d, 64, %d, false, %d>" % (
                          8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
                      # the same matrix instruction in a register-resident loop on this machine (operands
                      # with full significands spread like N(0,1); then all ones), and `achieved` as a

@@ -52,9 +52,12 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
 
 constexpr int kD = 128;               // head_dim
-constexpr int kBN = 64;               // KV tokens per LDS tile
 constexpr int kRowBytes = kD * 2;     // 256 B per token row
-constexpr int kTileBytes = kBN * kRowBytes;   // 16 KiB
+// KV tokens per LDS tile (template argument BN of the kernel): 64, or 32 as an option for the 2-wave
+// workgroups (64 queries) of small groups, whose four tiles then take 32 KiB so that four workgroups
+// (two waves per SIMD) share a compute unit instead of two - worth it for short lists, where a
+// workgroup's fixed cost weighs most; long lists run better on 64-key tiles (half as many barriers,
+// tile look-ups and load instructions per key).
 constexpr int kFragAhead = 2;         // an MFMA's LDS fragment is read this many MFMAs ahead of it
 
 // LDS tiles are unpadded [64 rows][16 chunks of 16 B]; the chunk index is XOR-swizzled per row so
@@ -128,14 +131,17 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
 // One query tile: tile t_in_head of its kind in (batch, head) bh.  DENSE: it is a tile of consecutive
 // query rows that walks the whole sequence (always in kDense, the prompt rows in kJoint), else a
 // tile of one query group.  sK / sV: the workgroup's two K and two V tile buffers in LDS.
-template <int NWAVES, int MODE, bool F16, int D, bool DENSE>
+template <int NWAVES, int BN, int MODE, bool F16, int D, bool DENSE>
 __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, const int t_in_head,
-                                          uint8_t (*sK)[kTileBytes], uint8_t (*sV)[kTileBytes]) {
+                                          uint8_t (*sK)[BN * kRowBytes], uint8_t (*sV)[BN * kRowBytes]) {
+    static_assert(BN == 64 || (BN == 32 && NWAVES == 2), "64-key tiles, or 32-key tiles for 2-wave workgroups");
+    constexpr int kBN = BN;
+    constexpr int kTileBytes = kBN * kRowBytes;
     static_assert(D == 128 || D == 64, "head_dim 128 or 64");
     using E = Elem<F16>;
     constexpr int NT = NWAVES * 64;
     constexpr int BM = NWAVES * 32;
-    constexpr int LPW = 16 / NWAVES;   // 1-KiB direct loads per wave per 16-KiB tile
+    constexpr int LPW = kBN / (4 * NWAVES);   // 1-KiB direct loads (4 token rows) per wave per tile
     constexpr bool dense = DENSE;
 
     extern __shared__ int32_t s_dyn[];   // [n_g] row offsets inside a group, then [max_kv] group origins (kRagged: and the two tables below)
@@ -176,7 +182,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
     int tiles_per_group = 1;
     int n_listed = 1;   // grouped tiles: entries in s_origin
     int n_lead = 0;     // grouped tile of a joint sequence: leading KV tiles that hold the prompt tokens
-    int mask_tile = -1, mask_valid = kBN;   // the one KV tile with fewer than 64 valid keys, if any
+    int mask_tile = -1, mask_valid = kBN;   // the one KV tile with fewer than kBN valid keys, if any
     // query rows of this wave: row i of its 32 is row q_first + i of the dense rows, resp. token
     // q_first + i of its group, whose first token is row q_base of the head
     uint32_t q_base = 0;
@@ -403,10 +409,10 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
         asm volatile("" : "+v"(k_addr[ks]));
     }
     auto k_frag = [&](int kbuf, int kb, int ks) -> frag8 {
-        return *(LDS_PTR(const frag8))(uintptr_t)(k_addr[ks] + kbuf * kTileBytes + kb * 32 * kRowBytes);
+        return *(LDS_PTR(const frag8))(uintptr_t)(k_addr[ks] + kbuf * kTileBytes + (kBN == 64 ? kb * 32 * kRowBytes : 0));
     };
     auto v_frag = [&](int vbuf, int kb, int s2, int db) -> frag8 {
-        const uint8_t* src = sV[vbuf] + v_lane_base + (32 * kb + 16 * s2) * kRowBytes + ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
+        const uint8_t* src = sV[vbuf] + v_lane_base + ((kBN == 64 ? 32 * kb : 0) + 16 * s2) * kRowBytes + ((4 * (db ^ tr_e) + v_chunk_lo) << 4);
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))src);
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(src + 8 * kRowBytes));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -414,7 +420,7 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
     auto mask_tail = [&](int kb) {   // the ragged tile: keys past the end of their run get weight 0
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int key = 32 * kb + 8 * (r >> 2) + 4 * half + (r & 3);
+            const int key = (kBN == 64 ? 32 * kb : 0) + 8 * (r >> 2) + 4 * half + (r & 3);
             if (key >= mask_valid) S[kb][r] = -INFINITY;
         }
     };
@@ -429,14 +435,14 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 // accumulator registers 4*rq .. 4*rq+3 hold 4 consecutive keys
-                const uint4 cc = *(const uint4*)&s_coord[j_m * kBN + 32 * kb + 8 * rq + 4 * half];
+                const uint4 cc = *(const uint4*)&s_coord[j_m * kBN + (kBN == 64 ? 32 * kb : 0) + 8 * rq + 4 * half];
                 if (!coord_inside(cc.x, lim)) S[kb][4 * rq] = -INFINITY;
                 if (!coord_inside(cc.y, lim)) S[kb][4 * rq + 1] = -INFINITY;
                 if (!coord_inside(cc.z, lim)) S[kb][4 * rq + 2] = -INFINITY;
                 if (!coord_inside(cc.w, lim)) S[kb][4 * rq + 3] = -INFINITY;
             }
         }
-        if (kb == 1 && ++j_m == tiles_per_group) { j_m = 0; ++gi_m; }
+        if ((kBN == 32 || kb == 1) && ++j_m == tiles_per_group) { j_m = 0; ++gi_m; }
     };
     // Weights are taken against a reference maximum m_ref that is only as fresh as it needs to be:
     // the common path computes exp2(c*s - c*m_ref) without looking at the block's own maximum and
@@ -482,9 +488,14 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
     // buffers of K(t-1) and V(t-2), which are refilled with K(t+1) and V(t) right away.
     // next_addrs(t): looks up where K(t+2) and V(t+1) lie (one tile before they are fetched, so that
     // the table reads never sit between a barrier and the loads that follow it).
+    // 32-key tiles (2-wave workgroups): a step is a single 32-key block, so PV trails QK by two tiles
+    // and V(t) is only fetched at barrier t+1, into the buffer V(t-2) was read from during step t;
+    // vb = where V(t-1) lies, one tile behind va.
+    TileAddr vb = va;
     auto next_addrs = [&](int t) {
         // (looked up unconditionally, also past the last tile, so that the table reads stay inside the
         // straight-line block around them instead of becoming a block of their own with its own waits)
+        if (kBN == 32) vb = va;
         if (dense) tile_addr(va, load_vcol, t + 1, gi_v, j_v);
         else v_from_k(va, ka);   // tile t + 1, whose K part has just been asked for
         tile_addr(ka, load_kcol, t + 2, gi_k, j_k);
@@ -493,7 +504,11 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
         __builtin_amdgcn_s_waitcnt(0);   // this wave's direct-to-LDS loads have landed
         __syncthreads();                 // ... everyone's have, and all reads of the buffers to refill are done
         if (t + 1 < n_tiles) issue_tile(Kh, sK[(t + 1) & 1], ka, k_on);
-        if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
+        if (kBN == 64) {
+            if (t < n_tiles) issue_tile(Vh, sV[t & 1], va, v_on);
+        } else {
+            if (t >= 1 && t - 1 < n_tiles) issue_tile(Vh, sV[(t - 1) & 1], vb, v_on);
+        }
     };
 
     // One step = the two half steps between two barriers, as one instruction stream.  Half KB (0, 1)
@@ -596,37 +611,69 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
     constexpr std::false_type no{};
     constexpr std::true_type yes{};
 
-    // tile 0: both QK products, and the weights of its first block against that block's maximum
-    {
-        swap_barrier(0);
-        next_addrs(0);
-        if (!kLists && mask_tile == 0) {
-            step(yes, c0, no, no, c0, no, no, c0, 0, 0, 0);
-            mask_tail(0);
-            step(no, c0, no, yes, c2, no, no, c0, 0, 0, 0);
-        } else {
-            step(yes, c0, no, yes, c2, no, no, c0, 0, 0, 0);
+    if constexpr (kBN == 64) {
+        // tile 0: both QK products, and the weights of its first block against that block's maximum
+        {
+            swap_barrier(0);
+            next_addrs(0);
+            if (!kLists && mask_tile == 0) {
+                step(yes, c0, no, no, c0, no, no, c0, 0, 0, 0);
+                mask_tail(0);
+                step(no, c0, no, yes, c2, no, no, c0, 0, 0, 0);
+            } else {
+                step(yes, c0, no, yes, c2, no, no, c0, 0, 0, 0);
+            }
         }
+        // tile t >= 1, first half: QK(t, keys 0..31), weights of (t-1, keys 32..63), PV of (t-1, keys 0..31);
+        // second half: QK(t, 32..63), weights of (t, 0..31), PV of (t-1, 32..63)
+        auto tile_step = [&](auto check, auto kbuf, int t) {   // kbuf = t & 1, as a compile-time constant
+            swap_barrier(t);
+            next_addrs(t);
+            step(yes, c1, yes, yes, c1, yes, check, kbuf, kbuf ^ 1, t - 1, t);
+        };
+        auto walk = [&](auto check) {
+            int t = 1;   // (two steps per trip: the LDS buffers of every step are compile-time constants)
+            for (; t + 1 < n_tiles; t += 2) {
+                tile_step(check, c1, t);
+                tile_step(check, c0, t + 1);
+            }
+            if (t < n_tiles) tile_step(check, c1, t);
+            swap_barrier(n_tiles);
+            step(no, c1, yes, no, c0, yes, check, c0, (n_tiles - 1) & 1, n_tiles - 1, n_tiles - 1);
+        };
+        if (!kLists && mask_tile >= 0) walk(yes);
+        else walk(no);
+    } else {
+        // 32-key tiles: the step behind barrier b forms the scores of tile b, weights tile b-1 and adds
+        // tile b-2 to O^T, all in the half (of S, pw and of the K and V buffers) of its parity.
+        auto block_step = [&](auto check, auto par, auto qk, auto sm, auto pv, int b) {
+            swap_barrier(b);
+            next_addrs(b);
+            if constexpr (decltype(par)::value == 0) step(qk, sm, pv, no, c0, no, check, c0, 0, b - 1, 0);
+            else step(no, c0, no, qk, sm, pv, check, c1, 1, 0, b - 1);
+        };
+        auto walk = [&](auto check) {
+            block_step(check, c0, yes, c0, no, 0);
+            if (n_tiles > 1) block_step(check, c1, yes, c2, no, 1);
+            else block_step(check, c1, no, c2, no, 1);
+            int b = 2;
+            for (; b + 1 < n_tiles; b += 2) {
+                block_step(check, c0, yes, c1, yes, b);
+                block_step(check, c1, yes, c1, yes, b + 1);
+            }
+            if (b < n_tiles) { block_step(check, c0, yes, c1, yes, b); ++b; }
+            // here b = max(n_tiles, 2); the last tile still has to be weighted (unless it was the first) and added
+            if (n_tiles >= 2) {
+                if (b & 1) block_step(check, c1, no, c1, yes, b);
+                else block_step(check, c0, no, c1, yes, b);
+                ++b;
+            }
+            if (b & 1) block_step(check, c1, no, c0, yes, b);
+            else block_step(check, c0, no, c0, yes, b);
+        };
+        if (!kLists && mask_tile >= 0) walk(yes);
+        else walk(no);
     }
-    // tile t >= 1, first half: QK(t, keys 0..31), weights of (t-1, keys 32..63), PV of (t-1, keys 0..31);
-    // second half: QK(t, 32..63), weights of (t, 0..31), PV of (t-1, 32..63)
-    auto tile_step = [&](auto check, auto kbuf, int t) {   // kbuf = t & 1, as a compile-time constant
-        swap_barrier(t);
-        next_addrs(t);
-        step(yes, c1, yes, yes, c1, yes, check, kbuf, kbuf ^ 1, t - 1, t);
-    };
-    auto walk = [&](auto check) {
-        int t = 1;   // (two steps per trip: the LDS buffers of every step are compile-time constants)
-        for (; t + 1 < n_tiles; t += 2) {
-            tile_step(check, c1, t);
-            tile_step(check, c0, t + 1);
-        }
-        if (t < n_tiles) tile_step(check, c1, t);
-        swap_barrier(n_tiles);
-        step(no, c1, yes, no, c0, yes, check, c0, (n_tiles - 1) & 1, n_tiles - 1, n_tiles - 1);
-    };
-    if (!kLists && mask_tile >= 0) walk(yes);
-    else walk(no);
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------------
     // In the accumulator layout a lane holds 4 consecutive head dims (8 bytes) at a time of ITS
@@ -696,10 +743,10 @@ __device__ __forceinline__ bool head_sync_tile(const AttnParams& p, int xcd, int
     t_in_head = ((xcd + bh) % kNumXcd) * per + (idx - bh * per);   // (rotated per head: border groups have shorter lists)
     return t_in_head < tph && bh < p.batch * p.heads;
 }
-template <int NWAVES, int MODE, bool F16, int D>
+template <int NWAVES, int BN, int MODE, bool F16, int D>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(AttnParams p) {
-    __shared__ __attribute__((aligned(1024))) uint8_t sK[2][kTileBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t sV[2][kTileBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t sK[2][BN * kRowBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t sV[2][BN * kRowBytes];
     const int xcd = blockIdx.x % kNumXcd, idx = blockIdx.x / kNumXcd;
     int bh, t_in_head;
     if constexpr (MODE == kJoint) {
@@ -708,44 +755,50 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(AttnParams p)
             const int tile = idx * kNumXcd + xcd;
             if (tile < p.n_dense_tiles) {
                 bh = (int)fdiv((uint32_t)tile, p.fd_tiles_per_head_dense);
-                attn_tile<NWAVES, MODE, F16, D, true>(p, bh, tile - bh * p.q_tiles_dense, sK, sV);
+                attn_tile<NWAVES, BN, MODE, F16, D, true>(p, bh, tile - bh * p.q_tiles_dense, sK, sV);
             }
         } else if (head_sync_tile<false>(p, xcd, idx - dense_per_xcd, bh, t_in_head)) {
-            attn_tile<NWAVES, MODE, F16, D, false>(p, bh, t_in_head, sK, sV);
+            attn_tile<NWAVES, BN, MODE, F16, D, false>(p, bh, t_in_head, sK, sV);
         }
     } else {
         if (head_sync_tile<MODE == kDense>(p, xcd, idx, bh, t_in_head))
-            attn_tile<NWAVES, MODE, F16, D, MODE == kDense>(p, bh, t_in_head, sK, sV);
+            attn_tile<NWAVES, BN, MODE, F16, D, MODE == kDense>(p, bh, t_in_head, sK, sV);
     }
 }
 
-template <int NWAVES, bool F16, int D>
+template <int NWAVES, int BN, bool F16, int D>
 inline hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) {
     const dim3 block(NWAVES * 64);
     const size_t dyn = mode == kDense ? 0 : sizeof(int32_t) * (mode == kRagged ? 2 : 1) * ((size_t)p.geo.group_tokens + p.max_kv);
     const int bh = p.batch * p.heads;
     const int grouped_blocks = kNumXcd * p.per_xcd * bh, dense_blocks = kNumXcd * p.per_xcd_dense * bh;
     if (mode == kRagged) {
-        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kRagged, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kRagged, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
     } else if (mode == kDense) {
-        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kDense, F16, D>), dim3(dense_blocks), block, dyn, stream, p);
+        if constexpr (NWAVES == 8)   // (the only tile height dense launches use)
+            hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kDense, F16, D>), dim3(dense_blocks), block, dyn, stream, p);
+        else
+            return hipErrorInvalidValue;
     } else if (mode == kGrouped) {
-        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kGrouped, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kGrouped, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
     } else {
         const int blocks = xcd_padded_blocks(p.n_dense_tiles) + grouped_blocks;
-        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
+        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
     }
     return hipGetLastError();
 }
 
 // p.q_tiles (and p.q_tiles_dense) were computed by the host for the query-tile height chosen here:
-// 256, 128 or 64 rows.
+// 256, 128 or 64 rows.  64-row workgroups take 32-key tiles unless the lists are long.
 template <bool F16, int D>
 inline hipError_t launch_by_tile(const AttnParams& p, int mode, hipStream_t stream) {
     const int bm = mode == kDense ? 256 : (p.geo.group_tokens / p.q_tiles);
-    if (bm == 256) return launch_one<8, F16, D>(p, mode, stream);
-    if (bm == 128) return launch_one<4, F16, D>(p, mode, stream);
-    return launch_one<2, F16, D>(p, mode, stream);
+    if (bm == 256) return launch_one<8, 64, F16, D>(p, mode, stream);
+    if (bm == 128) return launch_one<4, 64, F16, D>(p, mode, stream);
+    // (measured at 512x512 tokens in 8x8 groups: lists of 9 / 25 / 49 groups gain 16-19 % from the small
+    // tiles, the criss-cross lists of 127 groups lose 5 %)
+    if ((int64_t)p.max_kv * p.geo.group_tokens <= 64 * 64) return launch_one<2, 32, F16, D>(p, mode, stream);
+    return launch_one<2, 64, F16, D>(p, mode, stream);
 }
 
 }  // namespace grat
