@@ -279,6 +279,13 @@ def main():
         log(f"cpu oracle: {cpu}")
 
     traffic = None if n_glob or args.constant_data else measured_traffic(args.workload, args.pattern)
+    all_patterns = None
+    if extra:
+        fl = main_r["flops"] + sum(4.0 * w.head_dim * w.heads * w.batch * e["attended_pairs"] for e in extra.values())
+        ms = main_r["attn_kernel_ms_avg"] + sum(e["attn_kernel_ms_avg"] for e in extra.values())
+        all_patterns = {"patterns": [args.pattern] + list(extra), "kernel_ms": round(ms, 4),
+                        "tflops": round(fl / (ms * 1e-3) / 1e12, 2),
+                        "frac_of_peak": round(fl / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS, 4)}
     out = {
         "metric": "GRAT attn TFLOP/s (attended pairs) + speedup vs dense attn, 1 MI355X",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -314,6 +321,8 @@ def main():
         "speedup_vs_dense": round(dense["kernel_ms"] / main_r["attn_kernel_ms_avg"], 2) if dense else None,
         "paper_context": "paper: GRAT-B 35.8x over full attention at 8192x8192 on one NVIDIA A100",
         "other_patterns": extra,
+        # the workload's patterns together (one launch each): total attended-pair work / total kernel time
+        "all_patterns": all_patterns,
         "other_workloads": others_w,
     }
     print(json.dumps(out), flush=True)
