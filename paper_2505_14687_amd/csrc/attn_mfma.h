@@ -133,7 +133,8 @@ __device__ __forceinline__ bool coord_inside(uint32_t c, uint32_t lim) {
 // tile of one query group.  sK / sV: the workgroup's two K and two V tile buffers in LDS.
 template <int NWAVES, int BN, int MODE, bool F16, int D, bool DENSE>
 __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, const int t_in_head,
-                                          uint8_t (*sK)[BN * kRowBytes], uint8_t (*sV)[BN * kRowBytes]) {
+                                          uint8_t (*sK)[BN * kRowBytes], uint8_t (*sV)[BN * kRowBytes],
+                                          const int gamma_fixed = -1) {
     static_assert(BN == 64 || (BN == 32 && NWAVES == 2), "64-key tiles, or 32-key tiles for 2-wave workgroups");
     constexpr int kBN = BN;
     constexpr int kTileBytes = kBN * kRowBytes;
@@ -193,9 +194,15 @@ __device__ __forceinline__ void attn_tile(const AttnParams& p, const int bh, con
         if (p.n_tokens % kBN) { mask_tile = n_tiles - 1; mask_valid = p.n_tokens % kBN; }
         q_first = t_in_head * BM + wave * 32;
     } else {
-        const uint32_t u_group = fdiv((uint32_t)t_in_head, p.fd_q_tiles);
-        const int qt = t_in_head - (int)u_group * p.q_tiles;
-        const int gamma = strip_order_group_fast(u_group, geo.G[0] * geo.G[1], geo.G[2], p);
+        int qt, gamma;
+        if (gamma_fixed >= 0) {   // the caller has picked the group: t_in_head is the tile inside it
+            gamma = gamma_fixed;
+            qt = t_in_head;
+        } else {
+            const uint32_t u_group = fdiv((uint32_t)t_in_head, p.fd_q_tiles);
+            qt = t_in_head - (int)u_group * p.q_tiles;
+            gamma = strip_order_group_fast(u_group, geo.G[0] * geo.G[1], geo.G[2], p);
+        }
         const int n_g = geo.group_tokens;
         const int T12 = geo.T[1] * geo.T[2];
         // row of the first token of group gid, relative to the first grid row
@@ -743,6 +750,28 @@ __device__ __forceinline__ bool head_sync_tile(const AttnParams& p, int xcd, int
     t_in_head = ((xcd + bh) % kNumXcd) * per + (idx - bh * per);   // (rotated per head: border groups have shorter lists)
     return t_in_head < tph && bh < p.batch * p.heads;
 }
+// Small launches (p.longest_first; at most 64 groups): the hardware hands out workgroups in block order
+// and a launch of only a few rounds of workgroups ends when its last long one does, so the groups with
+// the longest lists go first and the short ones fill the tail.  Block b is query tile b % q_tiles of
+// (batch, head) (b / q_tiles) % (batch * heads) of the group whose list is the (b / (q_tiles * batch *
+// heads))-th longest (ties: lower id first); lane j ranks group j against the others, every wave for
+// itself.
+__device__ __forceinline__ bool longest_first_tile(const AttnParams& p, int b, int& bh, int& qt, int& gamma) {
+    const int G = p.geo.num_groups;
+    const int rank = (int)fdiv((uint32_t)b, p.fd_tiles_per_rank), rem = b - rank * p.batch * p.heads * p.q_tiles;
+    if (rank >= G) return false;
+    bh = (int)fdiv((uint32_t)rem, p.fd_q_tiles);
+    qt = rem - bh * p.q_tiles;
+    const int lane = threadIdx.x & 63;
+    const int key = lane < G ? min(max(p.kv_count[lane], 0), p.max_kv) * 64 + (63 - lane) : -1;
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < 64; ++k) r += __builtin_amdgcn_readlane(key, k) > key ? 1 : 0;
+    const uint64_t m = __ballot(lane < G && r == rank);   // (the keys differ, so exactly one lane)
+    gamma = __builtin_amdgcn_readfirstlane(__ffsll((long long)m) - 1);
+    return true;
+}
+
 template <int NWAVES, int BN, int MODE, bool F16, int D>
 __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(AttnParams p) {
     __shared__ __attribute__((aligned(1024))) uint8_t sK[2][BN * kRowBytes];
@@ -757,9 +786,17 @@ __global__ __launch_bounds__(NWAVES * 64, 2) void attn_mfma_kernel(AttnParams p)
                 bh = (int)fdiv((uint32_t)tile, p.fd_tiles_per_head_dense);
                 attn_tile<NWAVES, BN, MODE, F16, D, true>(p, bh, tile - bh * p.q_tiles_dense, sK, sV);
             }
+        } else if (p.longest_first) {
+            int qt, gamma;
+            if (longest_first_tile(p, (int)blockIdx.x - dense_per_xcd * kNumXcd, bh, qt, gamma))
+                attn_tile<NWAVES, BN, MODE, F16, D, false>(p, bh, qt, sK, sV, gamma);
         } else if (head_sync_tile<false>(p, xcd, idx - dense_per_xcd, bh, t_in_head)) {
             attn_tile<NWAVES, BN, MODE, F16, D, false>(p, bh, t_in_head, sK, sV);
         }
+    } else if (MODE != kDense && p.longest_first) {
+        int qt, gamma;
+        if (longest_first_tile(p, (int)blockIdx.x, bh, qt, gamma))
+            attn_tile<NWAVES, BN, MODE, F16, D, false>(p, bh, qt, sK, sV, gamma);
     } else {
         if (head_sync_tile<MODE == kDense>(p, xcd, idx, bh, t_in_head))
             attn_tile<NWAVES, BN, MODE, F16, D, MODE == kDense>(p, bh, t_in_head, sK, sV);

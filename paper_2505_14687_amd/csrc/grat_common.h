@@ -51,6 +51,8 @@ struct AttnParams {
     FastDiv fd_heads, fd_q_tiles;
     int32_t per_xcd, per_xcd_dense;   // tiles of one head that one XCD owns: ceil(tiles per head / 8), grouped and dense
     FastDiv fd_per_xcd, fd_per_xcd_dense;
+    int32_t longest_first;            // small grouped launches: tiles are handed out by list length, longest first
+    FastDiv fd_tiles_per_rank;        // by batch * heads * q_tiles
     FastDiv fd_strip, fd_strip_w, fd_strip_tail;   // strip order: by rows * strip_w, strip_w, width of the last strip
     int32_t strip_full;               // full strips: cols / strip_w
     FastDiv fd_g1, fd_g2, fd_G1, fd_G2;            // token in group -> box coordinates, group id -> group coordinates
