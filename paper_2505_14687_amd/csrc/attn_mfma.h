@@ -819,8 +819,12 @@ inline hipError_t launch_one(const AttnParams& p, int mode, hipStream_t stream) 
     } else if (mode == kGrouped) {
         hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kGrouped, F16, D>), dim3(grouped_blocks), block, dyn, stream, p);
     } else {
-        const int blocks = xcd_padded_blocks(p.n_dense_tiles) + grouped_blocks;
-        hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
+        if constexpr (BN == 64) {
+            const int blocks = xcd_padded_blocks(p.n_dense_tiles) + grouped_blocks;
+            hipLaunchKernelGGL((attn_mfma_kernel<NWAVES, BN, kJoint, F16, D>), dim3(blocks), block, dyn, stream, p);
+        } else {
+            return hipErrorInvalidValue;
+        }
     }
     return hipGetLastError();
 }
@@ -834,7 +838,8 @@ inline hipError_t launch_by_tile(const AttnParams& p, int mode, hipStream_t stre
     if (bm == 128) return launch_one<4, 64, F16, D>(p, mode, stream);
     // (measured at 512x512 tokens in 8x8 groups: lists of 9 / 25 / 49 groups gain 16-19 % from the small
     // tiles, the criss-cross lists of 127 groups lose 5 %)
-    if ((int64_t)p.max_kv * p.geo.group_tokens <= 64 * 64) return launch_one<2, 32, F16, D>(p, mode, stream);
+    // (not for joint sequences: that variant of the 32-key schedule does not fit the register file)
+    if (mode != kJoint && (int64_t)p.max_kv * p.geo.group_tokens <= 64 * 64) return launch_one<2, 32, F16, D>(p, mode, stream);
     return launch_one<2, 64, F16, D>(p, mode, stream);
 }
 
