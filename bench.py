@@ -35,6 +35,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def kernel_name(w, n_g, n_glob, pattern, radius):
+    """The instantiation the library launches for this workload (its rules, restated): template arguments
+    = waves per workgroup, keys per LDS tile, mode (0 grouped, 2 joint, 3 grid the group does not divide),
+    half?, head_dim."""
+    groups = int(np.prod([-(-t // g) for t, g in zip(w.grid, w.group)]))
+    waves = 8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2)
+    if waves == 8 and w.batch * w.heads * groups < 512:
+        waves = 4
+    ragged = any(t % g for t, g in zip(w.grid, w.group))
+    mode = 2 if n_glob else (3 if ragged else 0)
+    max_kv = grat.grat_block_list_shape(w.grid, w.group, pattern, radius)[1]
+    keys = 32 if waves == 2 and mode != 2 and max_kv * n_g <= 4096 else 64
+    return "grat::attn_mfma_kernel<%d, %d, %d, %s, %d>" % (waves, keys, mode, "true" if w.dtype == "f16" else "false", w.head_dim)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -311,8 +326,7 @@ def main():
                                        f"profiles/attn_mfma_{args.workload}_{args.pattern}.md: stored figure of a separate "
                                        "rocprofv3 --pmc run of this command, not measured in this run",
                      # template arguments: waves per workgroup, keys per LDS tile, mode (0 grouped, 2 joint), half?, head_dim
-                     "kernel": "grat::attn_mfma_kernel<%d, 64, %d, false, %d>" % (
-                         8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2), 2 if n_glob else 0, w.head_dim),
+                     "kernel": kernel_name(w, n_g, n_glob, pattern, radius),
                      # the same matrix instruction in a register-resident loop on this machine (operands
                      # with full significands spread like N(0,1); then all ones), and `achieved` as a
                      # fraction of the former
