@@ -39,6 +39,8 @@ def kernel_name(w, n_g, n_glob, pattern, radius):
     """The instantiation the library launches for this workload (its rules, restated): template arguments
     = waves per workgroup, keys per LDS tile, mode (0 grouped, 2 joint, 3 grid the group does not divide),
     half?, head_dim."""
+    import numpy as np
+    import paper_2505_14687_amd as grat
     groups = int(np.prod([-(-t // g) for t, g in zip(w.grid, w.group)]))
     waves = 8 if n_g % 256 == 0 else (4 if n_g % 128 == 0 else 2)
     if waves == 8 and w.batch * w.heads * groups < 512:

@@ -200,3 +200,20 @@ def test_probe_argument_errors():
     assert L.grat_probe_mfma(0, 2, fake, 256, 0, None) == 2 and L.grat_probe_mfma(2, 2, fake, 256, 4097, None) == 2
     assert L.grat_probe_mfma(0, 3, fake, 256, 16, None) == 2 and L.grat_probe_mfma(0, -1, fake, 256, 16, None) == 2
     assert L.grat_probe_mfma(1, 0, fake, 256, 16, None) == 6
+
+
+def test_bench_names_the_launched_instantiation():
+    """bench.py restates the library's launch rules to name the kernel in its roofline block (host only)."""
+    import numpy as np
+    import bench
+    from paper_2505_14687_amd import synth
+    names = {}
+    for wl, label in (("img8192", "B3"), ("img1024", "X"), ("video", "B3"), ("img8192_g8", "B3"), ("img8192_g8", "X")):
+        w = synth.WORKLOADS[wl]
+        pattern, radius = w.patterns[label]
+        names[(wl, label)] = bench.kernel_name(w, int(np.prod(w.group)), 0, pattern, radius)
+    assert names[("img8192", "B3")] == "grat::attn_mfma_kernel<8, 64, 0, false, 128>"
+    assert names[("img1024", "X")] == "grat::attn_mfma_kernel<4, 64, 0, false, 128>"
+    assert names[("video", "B3")] == "grat::attn_mfma_kernel<4, 64, 0, false, 128>"
+    assert names[("img8192_g8", "B3")] == "grat::attn_mfma_kernel<2, 32, 0, false, 128>"
+    assert names[("img8192_g8", "X")] == "grat::attn_mfma_kernel<2, 64, 0, false, 128>"
