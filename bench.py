@@ -211,12 +211,13 @@ def main():
     # N(0,1) rounded to bf16 like the main workload's, drawn on the device from a seeded generator)
     others_w = {}
     if not args.no_others and not args.constant_data and not n_glob and args.workload == "img8192":
-        for name, labels in (("img1024", ("B3", "X")), ("img2048", ("B3", "B5", "X", "dense")), ("video", ("B3", "X"))):
+        for name, labels in (("img1024", ("B3", "X")), ("img2048", ("B3", "B5", "X", "dense")), ("video", ("B3", "X")),
+                             ("video_paper", ("B3", "X")), ("img8192_g8", ("B3", "B5"))):
             ww = synth.WORKLOADS[name]
             gen = torch.Generator(device="cuda")
             gen.manual_seed(ww.seed)
             shape = (ww.batch, ww.heads, ww.n_tokens, ww.head_dim)
-            q, k, v = (torch.randn(shape, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+            q, k, v = (torch.randn(shape, device="cuda", generator=gen, dtype=torch.bfloat16) for _ in range(3))
             o = torch.empty_like(q)
             n_gw = int(np.prod(ww.group))
             res = {}
@@ -234,7 +235,7 @@ def main():
                 torch.cuda.synchronize()
                 # launches shorter than a millisecond are timed as they occur in a model: back to back
                 # (20 per pair of events), not one at a time out of an idle GPU
-                inner = 1 if pat == "dense" or name == "video" else 20
+                inner = 20 if name in ("img1024", "img2048") and pat != "dense" else 1
                 times = []
                 for _ in range(10):
                     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
